@@ -1,0 +1,218 @@
+/*
+ * zcgather -- GPU-issued sparse row gather from pinned, device-mapped host
+ * memory into a dense tensor in HBM, for one MI355X (gfx950).
+ *
+ * The method (paper Sections 3.1-3.3): the node-feature table stays in host
+ * memory that is page-locked and mapped into the GPU address space; for each
+ * minibatch the GPU itself reads the rows named by the sampled node-ID list
+ * over the host link ("zero-copy") and writes them densely into GPU memory,
+ * instead of a CPU gather into a staging buffer followed by a DMA copy.
+ *
+ * Conventions
+ *  - C ABI, no exceptions; every call returns an int status: ZCG_OK (0) or a
+ *    negative ZCG_E* code. zcg_strerror() names a code; when the code is
+ *    ZCG_EHIP, zcg_last_hip_error() gives the HIP error of the calling thread.
+ *  - "host" pointers are ordinary process addresses; "device" pointers are
+ *    addresses valid in GPU kernels (HBM or mapped host memory).
+ *  - Tables are row-major, contiguous: row r occupies bytes
+ *    [r*row_bytes, (r+1)*row_bytes), row_bytes = dim * element size.
+ *  - Handles may be used from several threads; creating and destroying
+ *    handles is serialised inside the library.
+ */
+#ifndef ZCGATHER_H
+#define ZCGATHER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------ */
+#define ZCG_OK 0
+#define ZCG_EINVAL (-1)  /* null pointer, non-positive size, bad option value   */
+#define ZCG_EDTYPE (-2)  /* dtype is not one of ZCG_F16 / ZCG_F32               */
+#define ZCG_EHANDLE (-3) /* not a live table handle (never made, or destroyed)  */
+#define ZCG_EHIP (-4)    /* a HIP runtime call failed; see zcg_last_hip_error() */
+#define ZCG_ENOMEM (-5)  /* host allocation failed                              */
+#define ZCG_EALIGN (-6)  /* pointer not aligned to the element size             */
+#define ZCG_EALIAS (-7)  /* output range overlaps the table                     */
+#define ZCG_ERANGE (-8)  /* an index is outside [0, n_rows) (host-side checks)  */
+
+/* ---- element types: only the size matters, payload bits are never read -- */
+#define ZCG_F16 1 /* 2-byte elements */
+#define ZCG_F32 2 /* 4-byte elements */
+
+/* ---- allocation flags for zcg_alloc_table ------------------------------ */
+#define ZCG_ALLOC_DEFAULT 0u     /* pinned, mapped, coherent (fine-grained)         */
+#define ZCG_ALLOC_NONCOHERENT 1u /* pinned, mapped, non-coherent: the GPU may cache
+                                    lines; host writes made while a kernel runs are
+                                    not guaranteed visible to it                      */
+#define ZCG_ALLOC_NUMA_USER 2u   /* keep the calling thread's NUMA policy           */
+
+/* ---- gather kernels (zcg_gather_variant / zcg_gather_ex) --------------- */
+#define ZCG_VARIANT_AUTO 0    /* ALIGNED when rows are unaligned to the line, else ROWVEC */
+#define ZCG_VARIANT_NAIVE 1   /* one element per lane over the flat output, no alignment
+                                 care: the paper's baseline kernel (Section 4.1.2 (c))  */
+#define ZCG_VARIANT_ROWVEC 2  /* a lane group per row, widest vector, loads start at the
+                                 row start                                              */
+#define ZCG_VARIANT_ALIGNED 3 /* a lane group per row; loads start at the line boundary
+                                 below the row start and are masked to the row, so every
+                                 wave load covers whole lines: the goal of the paper's
+                                 circular shift (Section 3.2.1), reads aligned, the
+                                 misalignment moved to the local writes                */
+#define ZCG_VARIANT_COUNT 4
+
+typedef struct zcg_table zcg_table; /* opaque */
+
+/* Launch options for zcg_gather_ex. Zero in any field means "library default". */
+typedef struct zcg_launch_opts {
+  int variant;     /* ZCG_VARIANT_*                                                   */
+  int max_blocks;  /* cap on the grid size (blocks of 256 lanes); the kernels stride   */
+  int unroll;      /* independent loads in flight per lane: 1, 2, 4 or 8               */
+  int line_bytes;  /* alignment target of ALIGNED: 32, 64, 128 or 256                  */
+  int nt_loads;    /* 1: non-temporal table loads, 2: plain loads                      */
+  int nt_stores;   /* 1: non-temporal output stores, 2: plain stores                   */
+  int vec_bytes;   /* cap on bytes per lane access: 2, 4, 8 or 16                      */
+} zcg_launch_opts;
+
+/* How one gather call is laid out on the GPU; filled by zcg_plan_gather. */
+typedef struct zcg_plan {
+  int variant;     /* resolved: NAIVE, ROWVEC or ALIGNED                               */
+  int vec_bytes;   /* bytes per lane access                                            */
+  int log2_group;  /* lanes per row = 1 << log2_group (row kernels)                    */
+  int iters;       /* group-wide passes needed to cover the widest (aligned) row span  */
+  int unroll;      /* independent loads in flight per lane                             */
+  int line_bytes;  /* alignment target (ALIGNED)                                       */
+  int nt_loads;    /* 0 / 1                                                            */
+  int nt_stores;   /* 0 / 1                                                            */
+  int blocks;      /* grid size, blocks of 256 lanes                                   */
+} zcg_plan;
+
+/* ---- errors ------------------------------------------------------------ */
+const char* zcg_strerror(int status);
+int zcg_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread */
+
+/*
+ * Step "map the table" (Section 3.1: page-lock an existing host buffer and map
+ * it into the GPU address space; no data is copied).
+ * host_ptr: host, CALLER-OWNED, n_rows*dim*elem bytes, must stay valid and
+ * unmoved until zcg_unregister_table. Pins with hipHostRegister (mapped,
+ * portable) on `device`. Errors: ZCG_EINVAL (null, n_rows<=0, dim<=0),
+ * ZCG_EDTYPE, ZCG_EALIGN, ZCG_EHIP (pin or map refused; nothing stays pinned).
+ */
+int zcg_register_table(void* host_ptr, int64_t n_rows, int64_t dim, int dtype, int device,
+                       zcg_table** out);
+
+/*
+ * Same step with LIBRARY-OWNED memory: hipHostMalloc (mapped, portable, plus
+ * `flags`). The caller fills the table through zcg_table_host_ptr(). Contents
+ * are uninitialised. Freed by zcg_unregister_table.
+ */
+int zcg_alloc_table(int64_t n_rows, int64_t dim, int dtype, unsigned flags, int device,
+                    zcg_table** out);
+
+/*
+ * Wrap a table that already lives in GPU memory (the paper's "all-in-GPU"
+ * comparison, Section 4.1.2 (d)): dev_ptr is device, CALLER-OWNED.
+ */
+int zcg_table_from_device(void* dev_ptr, int64_t n_rows, int64_t dim, int dtype, int device,
+                          zcg_table** out);
+
+/* Accessors; return NULL / 0 for a handle that is not live. */
+void* zcg_table_device_ptr(const zcg_table* t); /* pointer kernels read the table through */
+void* zcg_table_host_ptr(const zcg_table* t);   /* host address, NULL for device tables    */
+int64_t zcg_table_row_bytes(const zcg_table* t);
+int64_t zcg_table_n_rows(const zcg_table* t);
+
+/*
+ * Unpin / free. The handle is dead afterwards; a second call, or a pointer that
+ * was never a handle, returns ZCG_EHANDLE. The caller must first make sure no
+ * gather that reads the table is still running.
+ */
+int zcg_unregister_table(zcg_table* t);
+
+/*
+ * The gather (Section 3.2.1, Listing 2 semantics; Section 3.3: the index list
+ * is already on the GPU, the result lands in a GPU buffer):
+ *     out[i, c] = table[idx[i], c],  0 <= i < n_idx, 0 <= c < dim,
+ * bit for bit. Asynchronous: enqueues one kernel on `stream` (a hipStream_t
+ * passed as void*; NULL = the default stream) and returns; no allocation, no
+ * synchronisation, no host read of idx_dev.
+ *   idx_dev : device, n_idx int64, each in [0, n_rows). Out-of-range entries
+ *             are NOT checked here (undefined behaviour, as in the paper's
+ *             kernel); use zcg_validate_indices when in doubt.
+ *   out_dev : device, CALLER-OWNED, n_idx*row_bytes bytes, aligned to the
+ *             element size (16-byte alignment enables the widest accesses),
+ *             must not overlap the table (ZCG_EALIAS).
+ * The caller keeps idx_dev, out_dev and the table alive until the stream has
+ * passed the kernel. n_idx == 0 succeeds without a launch.
+ */
+int zcg_gather(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
+               void* stream);
+
+/* Same, forcing one kernel (ablation: Section 4.2 compares naive and aligned). */
+int zcg_gather_variant(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
+                       void* stream, int variant);
+
+/* Same, with every launch knob exposed (opts may be NULL). */
+int zcg_gather_ex(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
+                  void* stream, const zcg_launch_opts* opts);
+
+/*
+ * Host-only: the launch shape zcg_gather_ex would use for this table, output
+ * address and options (no GPU call is made). For tests and for reasoning about
+ * which bytes each wave load covers.
+ */
+int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
+                    const zcg_launch_opts* opts, zcg_plan* plan);
+
+/*
+ * Debug helper, SYNCHRONOUS: counts entries of idx_dev outside [0, n_rows) on
+ * the GPU, waits, and writes the count to *n_bad_host (host). Allocates and
+ * frees 8 bytes of device memory.
+ */
+int zcg_validate_indices(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* stream,
+                         int64_t* n_bad_host);
+
+/*
+ * The DMA-based method the paper argues against (Section 4.1.2 (b)): CPU
+ * threads gather the rows into a dense staging buffer, then ONE host-to-device
+ * copy moves it. Reported as a baseline.
+ *   idx_host       : host, n_idx int64; checked, ZCG_ERANGE on a bad entry
+ *   staging_pinned : host, CALLER-OWNED, >= n_idx*row_bytes bytes, should be
+ *                    pinned (hipHostMalloc) for the copy to be asynchronous
+ *   n_threads      : CPU threads for the gather (<=0: all available)
+ * The gather runs before the call returns; the copy is enqueued on `stream`
+ * and may still be in flight. Only for host-resident tables (ZCG_EINVAL else).
+ */
+int zcg_cpu_gather_memcpy(const zcg_table* t, const int64_t* idx_host, int64_t n_idx,
+                          void* staging_pinned, void* out_dev, int n_threads, void* stream);
+
+/*
+ * Strongest form of the same baseline: the list is cut into chunks of
+ * `chunk_rows` rows; the CPU gathers chunk k+1 while the copy of chunk k is in
+ * flight. staging_pinned must hold the whole gathered result.
+ */
+int zcg_cpu_gather_memcpy_chunked(const zcg_table* t, const int64_t* idx_host, int64_t n_idx,
+                                  void* staging_pinned, void* out_dev, int n_threads,
+                                  int64_t chunk_rows, void* stream);
+
+/*
+ * Link-peak probe (the denominator of the metric): median over `reps` timed
+ * pinned host-to-device hipMemcpyAsync copies of `bytes` bytes, after one
+ * warm-up, in GB/s (1e9 bytes). SYNCHRONOUS; allocates and frees its buffers.
+ */
+int zcg_measure_h2d(int64_t bytes, int reps, int device, double* gb_per_s);
+
+/* Pinned host scratch for callers without another allocator (staging buffers). */
+int zcg_pinned_alloc(int64_t bytes, void** host_ptr);
+int zcg_pinned_free(void* host_ptr);
+
+/* Library version, "major.minor". */
+const char* zcg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZCGATHER_H */

@@ -1,0 +1,15 @@
+"""MI355X-native zero-copy sparse feature gather.
+
+GPU wavefronts read the rows named by a minibatch's node-ID list straight out
+of a feature table kept in pinned, device-mapped host memory and write them as
+a dense tensor in HBM (the GPU-oriented data path of the paper's Section 3).
+The work is done by hand-written gfx950 kernels behind a C ABI
+(``include/zcgather.h``); this package is the thin Python binding.
+"""
+from .binding import (  # noqa: F401
+    ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER, F16, F32, VARIANT_ALIGNED, VARIANT_AUTO,
+    VARIANT_NAIVE, VARIANT_NAMES, VARIANT_ROWVEC, LaunchOpts, Table, ZcgError, alloc_table,
+    cpu_gather_memcpy, cpu_gather_memcpy_chunked, gather, gather_ex, gather_variant,
+    last_hip_error, load_library, measure_h2d, pinned_alloc, pinned_free, plan_gather,
+    register_table, strerror, table_from_device, unregister_table, validate_indices, version,
+)

@@ -1,0 +1,322 @@
+"""ctypes binding of libzcgather: argument marshalling only.
+
+Every function mirrors one C entry point of ``include/zcgather.h`` (same name
+without the ``zcg_`` prefix). Pointers may be given as integers or as objects
+with a ``data_ptr()`` method (torch tensors); streams as integers, objects with
+a ``cuda_stream`` attribute (torch streams) or None for the default stream.
+There is no CPU fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+# status codes / constants (include/zcgather.h)
+OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE = 0, -1, -2, -3, -4, -5, -6, -7, -8
+F16, F32 = 1, 2
+ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER = 0, 1, 2
+VARIANT_AUTO, VARIANT_NAIVE, VARIANT_ROWVEC, VARIANT_ALIGNED = 0, 1, 2, 3
+VARIANT_NAMES = {VARIANT_AUTO: "auto", VARIANT_NAIVE: "naive", VARIANT_ROWVEC: "rowvec",
+                 VARIANT_ALIGNED: "aligned"}
+_DTYPES = {"f16": F16, "f32": F32, F16: F16, F32: F32}
+_ELEM = {F16: 2, F32: 4}
+_NP = {F16: np.float16, F32: np.float32}
+
+EXPORTS = [
+    "zcg_strerror", "zcg_last_hip_error", "zcg_register_table", "zcg_alloc_table",
+    "zcg_table_from_device", "zcg_table_device_ptr", "zcg_table_host_ptr", "zcg_table_row_bytes",
+    "zcg_table_n_rows", "zcg_unregister_table", "zcg_gather", "zcg_gather_variant",
+    "zcg_gather_ex", "zcg_plan_gather", "zcg_validate_indices", "zcg_cpu_gather_memcpy",
+    "zcg_cpu_gather_memcpy_chunked", "zcg_measure_h2d", "zcg_pinned_alloc", "zcg_pinned_free",
+    "zcg_version",
+]
+
+
+class LaunchOpts(ctypes.Structure):
+    """zcg_launch_opts; zero in a field means the library default."""
+    _fields_ = [("variant", ctypes.c_int), ("max_blocks", ctypes.c_int), ("unroll", ctypes.c_int),
+                ("line_bytes", ctypes.c_int), ("nt_loads", ctypes.c_int),
+                ("nt_stores", ctypes.c_int), ("vec_bytes", ctypes.c_int)]
+
+
+class Plan(ctypes.Structure):
+    """zcg_plan."""
+    _fields_ = [("variant", ctypes.c_int), ("vec_bytes", ctypes.c_int),
+                ("log2_group", ctypes.c_int), ("iters", ctypes.c_int), ("unroll", ctypes.c_int),
+                ("line_bytes", ctypes.c_int), ("nt_loads", ctypes.c_int),
+                ("nt_stores", ctypes.c_int), ("blocks", ctypes.c_int)]
+
+    def as_dict(self) -> dict:
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class ZcgError(RuntimeError):
+    def __init__(self, status: int, what: str, hip_error: int = 0):
+        self.status, self.hip_error = status, hip_error
+        msg = f"{what}: {strerror(status)} ({status})"
+        if status == EHIP:
+            msg += f", hipError_t={hip_error}"
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; build it first only if nothing is built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, i64, i32, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint
+    pvp = ctypes.POINTER(ctypes.c_void_p)
+    sigs = {
+        "zcg_strerror": (ctypes.c_char_p, [i32]),
+        "zcg_version": (ctypes.c_char_p, []),
+        "zcg_last_hip_error": (i32, []),
+        "zcg_register_table": (i32, [vp, i64, i64, i32, i32, pvp]),
+        "zcg_alloc_table": (i32, [i64, i64, i32, u32, i32, pvp]),
+        "zcg_table_from_device": (i32, [vp, i64, i64, i32, i32, pvp]),
+        "zcg_table_device_ptr": (vp, [vp]),
+        "zcg_table_host_ptr": (vp, [vp]),
+        "zcg_table_row_bytes": (i64, [vp]),
+        "zcg_table_n_rows": (i64, [vp]),
+        "zcg_unregister_table": (i32, [vp]),
+        "zcg_gather": (i32, [vp, vp, i64, vp, vp]),
+        "zcg_gather_variant": (i32, [vp, vp, i64, vp, vp, i32]),
+        "zcg_gather_ex": (i32, [vp, vp, i64, vp, vp, ctypes.POINTER(LaunchOpts)]),
+        "zcg_plan_gather": (i32, [vp, i64, vp, ctypes.POINTER(LaunchOpts), ctypes.POINTER(Plan)]),
+        "zcg_validate_indices": (i32, [vp, vp, i64, vp, ctypes.POINTER(i64)]),
+        "zcg_cpu_gather_memcpy": (i32, [vp, vp, i64, vp, vp, i32, vp]),
+        "zcg_cpu_gather_memcpy_chunked": (i32, [vp, vp, i64, vp, vp, i32, i64, vp]),
+        "zcg_measure_h2d": (i32, [i64, i32, i32, ctypes.POINTER(ctypes.c_double)]),
+        "zcg_pinned_alloc": (i32, [i64, pvp]),
+        "zcg_pinned_free": (i32, [vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().zcg_strerror(status).decode()
+
+
+def version() -> str:
+    return load_library().zcg_version().decode()
+
+
+def last_hip_error() -> int:
+    return int(load_library().zcg_last_hip_error())
+
+
+def _check(status: int, what: str) -> None:
+    if status != OK:
+        raise ZcgError(status, what, last_hip_error() if status == EHIP else 0)
+
+
+def _ptr(x) -> int:
+    if x is None:
+        return 0
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr())
+    return int(x)
+
+
+def _stream(s) -> int:
+    if s is None:
+        return 0
+    if hasattr(s, "cuda_stream"):
+        return int(s.cuda_stream)
+    return int(s)
+
+
+def _n_idx(idx, n_idx: Optional[int]) -> int:
+    if n_idx is not None:
+        return int(n_idx)
+    if hasattr(idx, "numel"):
+        return int(idx.numel())
+    if hasattr(idx, "size"):
+        return int(idx.size)
+    raise TypeError("n_idx is required when idx is a raw pointer")
+
+
+def _check_idx_tensor(idx) -> None:
+    # torch tensors carry enough to catch the common marshalling mistakes early
+    if hasattr(idx, "dtype") and hasattr(idx, "is_contiguous"):
+        if "int64" not in str(idx.dtype):
+            raise TypeError("index list must be int64")
+        if not idx.is_contiguous():
+            raise ValueError("index list must be contiguous")
+
+
+@dataclass
+class Table:
+    """A live table handle. ``close()`` (or the context manager) unpins / frees it."""
+    handle: int
+    n_rows: int
+    dim: int
+    dtype: int
+
+    @property
+    def elem_bytes(self) -> int:
+        return _ELEM[self.dtype]
+
+    @property
+    def row_bytes(self) -> int:
+        return self.dim * self.elem_bytes
+
+    @property
+    def device_ptr(self) -> int:
+        return int(load_library().zcg_table_device_ptr(self.handle) or 0)
+
+    @property
+    def host_ptr(self) -> int:
+        return int(load_library().zcg_table_host_ptr(self.handle) or 0)
+
+    def host_array(self) -> np.ndarray:
+        """numpy view [n_rows, dim] of a host-resident table (no copy)."""
+        p = self.host_ptr
+        if not p:
+            raise ValueError("table has no host address")
+        n = self.n_rows * self.dim
+        buf = (ctypes.c_char * (n * self.elem_bytes)).from_address(p)
+        return np.frombuffer(buf, dtype=_NP[self.dtype], count=n).reshape(self.n_rows, self.dim)
+
+    def close(self) -> None:
+        if self.handle:
+            h, self.handle = self.handle, 0
+            _check(load_library().zcg_unregister_table(h), "zcg_unregister_table")
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+
+def _new_table(status: int, what: str, out: ctypes.c_void_p, n_rows, dim, dtype) -> Table:
+    _check(status, what)
+    return Table(int(out.value), int(n_rows), int(dim), dtype)
+
+
+def register_table(host, n_rows: int, dim: int, dtype, device: int = 0) -> Table:
+    """Pin + map caller-owned host memory (a numpy array or an address)."""
+    addr = host.ctypes.data if isinstance(host, np.ndarray) else _ptr(host)
+    dt = _DTYPES.get(dtype, dtype)
+    out = ctypes.c_void_p()
+    rc = load_library().zcg_register_table(addr, n_rows, dim, dt, device, ctypes.byref(out))
+    return _new_table(rc, "zcg_register_table", out, n_rows, dim, dt)
+
+
+def alloc_table(n_rows: int, dim: int, dtype, flags: int = ALLOC_DEFAULT, device: int = 0) -> Table:
+    dt = _DTYPES.get(dtype, dtype)
+    out = ctypes.c_void_p()
+    rc = load_library().zcg_alloc_table(n_rows, dim, dt, flags, device, ctypes.byref(out))
+    return _new_table(rc, "zcg_alloc_table", out, n_rows, dim, dt)
+
+
+def table_from_device(dev, n_rows: int, dim: int, dtype, device: int = 0) -> Table:
+    dt = _DTYPES.get(dtype, dtype)
+    out = ctypes.c_void_p()
+    rc = load_library().zcg_table_from_device(_ptr(dev), n_rows, dim, dt, device, ctypes.byref(out))
+    return _new_table(rc, "zcg_table_from_device", out, n_rows, dim, dt)
+
+
+def unregister_table(table: Table) -> None:
+    table.close()
+
+
+def gather(table: Table, idx_dev, out_dev, n_idx: Optional[int] = None, stream=None) -> None:
+    _check_idx_tensor(idx_dev)
+    rc = load_library().zcg_gather(table.handle, _ptr(idx_dev), _n_idx(idx_dev, n_idx),
+                                   _ptr(out_dev), _stream(stream))
+    _check(rc, "zcg_gather")
+
+
+def gather_variant(table: Table, idx_dev, out_dev, variant: int, n_idx: Optional[int] = None,
+                   stream=None) -> None:
+    _check_idx_tensor(idx_dev)
+    rc = load_library().zcg_gather_variant(table.handle, _ptr(idx_dev), _n_idx(idx_dev, n_idx),
+                                           _ptr(out_dev), _stream(stream), variant)
+    _check(rc, "zcg_gather_variant")
+
+
+def gather_ex(table: Table, idx_dev, out_dev, opts: Optional[LaunchOpts] = None,
+              n_idx: Optional[int] = None, stream=None) -> None:
+    _check_idx_tensor(idx_dev)
+    rc = load_library().zcg_gather_ex(table.handle, _ptr(idx_dev), _n_idx(idx_dev, n_idx),
+                                      _ptr(out_dev), _stream(stream),
+                                      ctypes.byref(opts) if opts is not None else None)
+    _check(rc, "zcg_gather_ex")
+
+
+def plan_gather(table: Table, n_idx: int, out_dev, opts: Optional[LaunchOpts] = None) -> dict:
+    plan = Plan()
+    rc = load_library().zcg_plan_gather(table.handle, n_idx, _ptr(out_dev),
+                                        ctypes.byref(opts) if opts is not None else None,
+                                        ctypes.byref(plan))
+    _check(rc, "zcg_plan_gather")
+    return plan.as_dict()
+
+
+def validate_indices(table: Table, idx_dev, n_idx: Optional[int] = None, stream=None) -> int:
+    _check_idx_tensor(idx_dev)
+    n_bad = ctypes.c_int64(0)
+    rc = load_library().zcg_validate_indices(table.handle, _ptr(idx_dev), _n_idx(idx_dev, n_idx),
+                                             _stream(stream), ctypes.byref(n_bad))
+    _check(rc, "zcg_validate_indices")
+    return int(n_bad.value)
+
+
+def _host_idx(idx_host) -> np.ndarray:
+    a = np.ascontiguousarray(idx_host, dtype=np.int64)
+    if a.ndim != 1:
+        raise ValueError("index list must be 1-D")
+    return a
+
+
+def cpu_gather_memcpy(table: Table, idx_host, staging_pinned, out_dev, n_threads: int = 0,
+                      stream=None) -> None:
+    a = _host_idx(idx_host)
+    rc = load_library().zcg_cpu_gather_memcpy(table.handle, a.ctypes.data, a.size,
+                                              _ptr(staging_pinned), _ptr(out_dev), n_threads,
+                                              _stream(stream))
+    _check(rc, "zcg_cpu_gather_memcpy")
+
+
+def cpu_gather_memcpy_chunked(table: Table, idx_host, staging_pinned, out_dev, chunk_rows: int,
+                              n_threads: int = 0, stream=None) -> None:
+    a = _host_idx(idx_host)
+    rc = load_library().zcg_cpu_gather_memcpy_chunked(table.handle, a.ctypes.data, a.size,
+                                                      _ptr(staging_pinned), _ptr(out_dev),
+                                                      n_threads, chunk_rows, _stream(stream))
+    _check(rc, "zcg_cpu_gather_memcpy_chunked")
+
+
+def measure_h2d(n_bytes: int, reps: int = 10, device: int = 0) -> float:
+    """Median pinned host-to-device copy bandwidth in GB/s (1e9 bytes)."""
+    g = ctypes.c_double(0.0)
+    _check(load_library().zcg_measure_h2d(n_bytes, reps, device, ctypes.byref(g)), "zcg_measure_h2d")
+    return float(g.value)
+
+
+def pinned_alloc(n_bytes: int) -> int:
+    p = ctypes.c_void_p()
+    _check(load_library().zcg_pinned_alloc(n_bytes, ctypes.byref(p)), "zcg_pinned_alloc")
+    return int(p.value)
+
+
+def pinned_free(ptr: int) -> None:
+    _check(load_library().zcg_pinned_free(ptr), "zcg_pinned_free")

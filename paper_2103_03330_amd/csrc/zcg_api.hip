@@ -1,0 +1,303 @@
+// C-ABI entry points of libzcgather: table handles, the gather dispatch, the
+// index check and the link-peak probe. Kernels live in zcg_kernels.hip, the
+// CPU-gather baseline in zcg_cpu_baseline.hip.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <mutex>
+#include <new>
+#include <unordered_set>
+#include <vector>
+
+#include "zcg_internal.h"
+
+namespace {
+
+std::mutex g_mu;
+std::unordered_set<const zcg_table*> g_live;
+thread_local int t_last_hip = 0;
+
+int elem_of(int dtype) {
+  if (dtype == ZCG_F16) return 2;
+  if (dtype == ZCG_F32) return 4;
+  return 0;
+}
+
+int check_shape(int64_t n_rows, int64_t dim, int dtype, zcg_table** out, int* elem) {
+  if (!out) return ZCG_EINVAL;
+  *out = nullptr;
+  *elem = elem_of(dtype);
+  if (!*elem) return ZCG_EDTYPE;
+  if (n_rows <= 0 || dim <= 0) return ZCG_EINVAL;
+  if (dim > (INT64_MAX / *elem) || n_rows > INT64_MAX / (dim * *elem)) return ZCG_EINVAL;
+  return ZCG_OK;
+}
+
+zcg_table* make_handle(int kind, int dtype, int elem, int device, void* host, void* dev,
+                       int64_t n_rows, int64_t dim) {
+  zcg_table* t = new (std::nothrow) zcg_table;
+  if (!t) return nullptr;
+  t->kind = kind; t->dtype = dtype; t->elem = elem; t->device = device;
+  t->host = host; t->dev = dev; t->n_rows = n_rows; t->dim = dim;
+  t->row_bytes = dim * elem;
+  std::lock_guard<std::mutex> lk(g_mu);
+  g_live.insert(t);
+  return t;
+}
+
+// Makes `device` current for the lifetime of the object, then restores.
+struct DeviceScope {
+  int prev = -1;
+  hipError_t err;
+  explicit DeviceScope(int device) {
+    err = hipGetDevice(&prev);
+    if (err == hipSuccess && prev != device) err = hipSetDevice(device);
+  }
+  ~DeviceScope() {
+    int cur = -1;
+    if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+  }
+};
+
+}  // namespace
+
+bool zcg_is_live(const zcg_table* t) {
+  if (!t) return false;
+  std::lock_guard<std::mutex> lk(g_mu);
+  return g_live.count(t) != 0;
+}
+
+int zcg_fail_hip(hipError_t e) {
+  t_last_hip = (int)e;
+  (void)hipGetLastError();  // do not leave a sticky error for the caller's next HIP call
+  return ZCG_EHIP;
+}
+
+extern "C" {
+
+const char* zcg_version(void) { return "0.1"; }
+
+const char* zcg_strerror(int status) {
+  switch (status) {
+    case ZCG_OK: return "ok";
+    case ZCG_EINVAL: return "invalid argument";
+    case ZCG_EDTYPE: return "unsupported element type";
+    case ZCG_EHANDLE: return "not a live table handle";
+    case ZCG_EHIP: return "HIP runtime call failed";
+    case ZCG_ENOMEM: return "out of host memory";
+    case ZCG_EALIGN: return "pointer not aligned to the element size";
+    case ZCG_EALIAS: return "output overlaps the table";
+    case ZCG_ERANGE: return "index out of range";
+    default: return "unknown status";
+  }
+}
+
+int zcg_last_hip_error(void) { return t_last_hip; }
+
+int zcg_register_table(void* host_ptr, int64_t n_rows, int64_t dim, int dtype, int device,
+                       zcg_table** out) {
+  int elem;
+  int rc = check_shape(n_rows, dim, dtype, out, &elem);
+  if (rc) return rc;
+  if (!host_ptr || device < 0) return ZCG_EINVAL;
+  if ((uintptr_t)host_ptr % (uintptr_t)elem) return ZCG_EALIGN;
+  DeviceScope scope(device);
+  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
+  const size_t bytes = (size_t)(n_rows * dim * elem);
+  hipError_t e = hipHostRegister(host_ptr, bytes, hipHostRegisterMapped | hipHostRegisterPortable);
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  void* dev = nullptr;
+  e = hipHostGetDevicePointer(&dev, host_ptr, 0);
+  if (e != hipSuccess || !dev) {
+    (void)hipHostUnregister(host_ptr);
+    return zcg_fail_hip(e != hipSuccess ? e : hipErrorInvalidValue);
+  }
+  zcg_table* t = make_handle(ZCG_KIND_REGISTERED, dtype, elem, device, host_ptr, dev, n_rows, dim);
+  if (!t) {
+    (void)hipHostUnregister(host_ptr);
+    return ZCG_ENOMEM;
+  }
+  *out = t;
+  return ZCG_OK;
+}
+
+int zcg_alloc_table(int64_t n_rows, int64_t dim, int dtype, unsigned flags, int device,
+                    zcg_table** out) {
+  int elem;
+  int rc = check_shape(n_rows, dim, dtype, out, &elem);
+  if (rc) return rc;
+  if (device < 0 || (flags & ~(ZCG_ALLOC_NONCOHERENT | ZCG_ALLOC_NUMA_USER))) return ZCG_EINVAL;
+  DeviceScope scope(device);
+  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
+  unsigned hip_flags = hipHostMallocMapped | hipHostMallocPortable;
+  hip_flags |= (flags & ZCG_ALLOC_NONCOHERENT) ? hipHostMallocNonCoherent : hipHostMallocCoherent;
+  if (flags & ZCG_ALLOC_NUMA_USER) hip_flags |= hipHostMallocNumaUser;
+  void* host = nullptr;
+  hipError_t e = hipHostMalloc(&host, (size_t)(n_rows * dim * elem), hip_flags);
+  if (e != hipSuccess || !host) return zcg_fail_hip(e != hipSuccess ? e : hipErrorOutOfMemory);
+  void* dev = nullptr;
+  e = hipHostGetDevicePointer(&dev, host, 0);
+  if (e != hipSuccess || !dev) {
+    (void)hipHostFree(host);
+    return zcg_fail_hip(e != hipSuccess ? e : hipErrorInvalidValue);
+  }
+  zcg_table* t = make_handle(ZCG_KIND_ALLOCATED, dtype, elem, device, host, dev, n_rows, dim);
+  if (!t) {
+    (void)hipHostFree(host);
+    return ZCG_ENOMEM;
+  }
+  *out = t;
+  return ZCG_OK;
+}
+
+int zcg_table_from_device(void* dev_ptr, int64_t n_rows, int64_t dim, int dtype, int device,
+                          zcg_table** out) {
+  int elem;
+  int rc = check_shape(n_rows, dim, dtype, out, &elem);
+  if (rc) return rc;
+  if (!dev_ptr || device < 0) return ZCG_EINVAL;
+  if ((uintptr_t)dev_ptr % (uintptr_t)elem) return ZCG_EALIGN;
+  zcg_table* t = make_handle(ZCG_KIND_DEVICE, dtype, elem, device, nullptr, dev_ptr, n_rows, dim);
+  if (!t) return ZCG_ENOMEM;
+  *out = t;
+  return ZCG_OK;
+}
+
+void* zcg_table_device_ptr(const zcg_table* t) { return zcg_is_live(t) ? t->dev : nullptr; }
+void* zcg_table_host_ptr(const zcg_table* t) { return zcg_is_live(t) ? t->host : nullptr; }
+int64_t zcg_table_row_bytes(const zcg_table* t) { return zcg_is_live(t) ? t->row_bytes : 0; }
+int64_t zcg_table_n_rows(const zcg_table* t) { return zcg_is_live(t) ? t->n_rows : 0; }
+
+int zcg_unregister_table(zcg_table* t) {
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!t || g_live.erase(t) == 0) return ZCG_EHANDLE;
+  }
+  int rc = ZCG_OK;
+  if (t->kind == ZCG_KIND_REGISTERED) {
+    hipError_t e = hipHostUnregister(t->host);
+    if (e != hipSuccess) rc = zcg_fail_hip(e);
+  } else if (t->kind == ZCG_KIND_ALLOCATED) {
+    hipError_t e = hipHostFree(t->host);
+    if (e != hipSuccess) rc = zcg_fail_hip(e);
+  }
+  delete t;
+  return rc;
+}
+
+int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
+                    const zcg_launch_opts* opts, zcg_plan* plan) {
+  if (!zcg_is_live(t)) return ZCG_EHANDLE;
+  return zcg_make_plan(t->row_bytes, t->elem, (uintptr_t)t->dev, (uintptr_t)out_dev, n_idx,
+                       t->kind != ZCG_KIND_DEVICE, opts, plan);
+}
+
+int zcg_gather_ex(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
+                  void* stream, const zcg_launch_opts* opts) {
+  if (!zcg_is_live(t)) return ZCG_EHANDLE;
+  if (n_idx < 0) return ZCG_EINVAL;
+  if (n_idx == 0) return ZCG_OK;
+  if (!idx_dev || !out_dev) return ZCG_EINVAL;
+  if ((uintptr_t)idx_dev % 8) return ZCG_EALIGN;
+  if (n_idx > INT64_MAX / t->row_bytes) return ZCG_EINVAL;
+  const uintptr_t o0 = (uintptr_t)out_dev, o1 = o0 + (uintptr_t)(n_idx * t->row_bytes);
+  const uintptr_t t0 = (uintptr_t)t->dev, t1 = t0 + (uintptr_t)(t->n_rows * t->row_bytes);
+  if (o0 < t1 && t0 < o1) return ZCG_EALIAS;
+  zcg_plan plan;
+  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, t->kind != ZCG_KIND_DEVICE, opts,
+                         &plan);
+  if (rc) return rc;
+  hipError_t e = zcg_launch_gather(plan, t->dev, idx_dev, n_idx, out_dev, t->row_bytes, t->elem,
+                                   static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
+}
+
+int zcg_gather(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
+               void* stream) {
+  return zcg_gather_ex(t, idx_dev, n_idx, out_dev, stream, nullptr);
+}
+
+int zcg_gather_variant(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
+                       void* stream, int variant) {
+  zcg_launch_opts o = {};
+  o.variant = variant;
+  return zcg_gather_ex(t, idx_dev, n_idx, out_dev, stream, &o);
+}
+
+int zcg_validate_indices(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* stream,
+                         int64_t* n_bad_host) {
+  if (!zcg_is_live(t)) return ZCG_EHANDLE;
+  if (!n_bad_host || n_idx < 0 || (n_idx > 0 && !idx_dev)) return ZCG_EINVAL;
+  *n_bad_host = 0;
+  if (n_idx == 0) return ZCG_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned long long* d = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&d), sizeof(*d));
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  unsigned long long h = 0;
+  e = hipMemcpyAsync(d, &h, sizeof(h), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e == hipSuccess) e = zcg_launch_validate(idx_dev, n_idx, t->n_rows, d, s);
+  if (e == hipSuccess) e = hipMemcpyAsync(&h, d, sizeof(h), hipMemcpyDeviceToHost, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(d);
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  *n_bad_host = (int64_t)h;
+  return ZCG_OK;
+}
+
+int zcg_measure_h2d(int64_t bytes, int reps, int device, double* gb_per_s) {
+  if (bytes <= 0 || reps < 1 || reps > 1000 || device < 0 || !gb_per_s) return ZCG_EINVAL;
+  *gb_per_s = 0.0;
+  DeviceScope scope(device);
+  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
+  void *h = nullptr, *d = nullptr;
+  hipStream_t s = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  std::vector<float> ms;
+  hipError_t e = hipHostMalloc(&h, (size_t)bytes, hipHostMallocDefault);
+  if (e == hipSuccess) e = hipMalloc(&d, (size_t)bytes);
+  if (e == hipSuccess) e = hipStreamCreate(&s);
+  if (e == hipSuccess) e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e == hipSuccess) {
+    // touch the pages so the first timed copy does not pay for faults
+    for (int64_t i = 0; i < bytes; i += 4096) static_cast<volatile char*>(h)[i] = (char)i;
+    e = hipMemcpyAsync(d, h, (size_t)bytes, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+  }
+  for (int r = 0; r < reps && e == hipSuccess; ++r) {
+    e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(d, h, (size_t)bytes, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+    if (e == hipSuccess) ms.push_back(t);
+  }
+  if (e1) (void)hipEventDestroy(e1);
+  if (e0) (void)hipEventDestroy(e0);
+  if (s) (void)hipStreamDestroy(s);
+  if (d) (void)hipFree(d);
+  if (h) (void)hipHostFree(h);
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  std::sort(ms.begin(), ms.end());
+  const double med = ms[ms.size() / 2];
+  *gb_per_s = (double)bytes / (med * 1e-3) / 1e9;
+  return ZCG_OK;
+}
+
+int zcg_pinned_alloc(int64_t bytes, void** host_ptr) {
+  if (bytes <= 0 || !host_ptr) return ZCG_EINVAL;
+  *host_ptr = nullptr;
+  hipError_t e = hipHostMalloc(host_ptr, (size_t)bytes, hipHostMallocDefault);
+  return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
+}
+
+int zcg_pinned_free(void* host_ptr) {
+  if (!host_ptr) return ZCG_EINVAL;
+  hipError_t e = hipHostFree(host_ptr);
+  return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
+}
+
+}  // extern "C"

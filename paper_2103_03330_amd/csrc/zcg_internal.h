@@ -1,0 +1,37 @@
+// Internal declarations shared by the translation units of libzcgather.
+#ifndef ZCG_INTERNAL_H
+#define ZCG_INTERNAL_H
+
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#include "zcgather.h"
+
+enum zcg_kind { ZCG_KIND_REGISTERED = 1, ZCG_KIND_ALLOCATED = 2, ZCG_KIND_DEVICE = 3 };
+
+struct zcg_table {
+  int kind;
+  int dtype;
+  int elem;  // bytes per element
+  int device;
+  void* host;  // nullptr for device tables
+  void* dev;   // address kernels use
+  int64_t n_rows;
+  int64_t dim;
+  int64_t row_bytes;
+};
+
+// zcg_api.hip
+bool zcg_is_live(const zcg_table* t);
+int zcg_fail_hip(hipError_t e);  // records e for zcg_last_hip_error, returns ZCG_EHIP
+
+// zcg_kernels.hip
+int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t out_addr,
+                  int64_t n_idx, bool host_resident, const zcg_launch_opts* opts, zcg_plan* plan);
+hipError_t zcg_launch_gather(const zcg_plan& plan, const void* table, const int64_t* idx,
+                             int64_t n_idx, void* out, int64_t row_bytes, int elem,
+                             hipStream_t stream);
+hipError_t zcg_launch_validate(const int64_t* idx, int64_t n_idx, int64_t n_rows,
+                               unsigned long long* n_bad_dev, hipStream_t stream);
+
+#endif

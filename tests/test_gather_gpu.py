@@ -1,0 +1,229 @@
+"""GPU parity: the HIP gather, called through the C ABI, against the CPU oracle,
+bit for bit, on the same seeded inputs. Integer/byte work: the bar is exact."""
+import numpy as np
+import pytest
+
+import zcg_workload as wl
+from oracle import gather as oracle_gather
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+z = pytest.importorskip("paper_2103_03330_amd")
+
+ALL_VARIANTS = [z.VARIANT_AUTO, z.VARIANT_NAIVE, z.VARIANT_ROWVEC, z.VARIANT_ALIGNED]
+TORCH_DT = {"f16": torch.float16, "f32": torch.float32}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: torch.cuda.is_available() is False")
+    z.load_library()
+    torch.cuda.set_device(0)
+
+
+def host_table(n_rows, dim, dtype, seed, mode=wl.FILL_UNIFORM, flags=z.ALLOC_DEFAULT):
+    t = z.alloc_table(n_rows, dim, dtype, flags)
+    wl.fill_table_ptr(t.host_ptr, n_rows, dim, dtype, seed, mode)
+    return t
+
+
+def run_gather(table, idx_np, dtype, opts=None, out=None):
+    idx_dev = torch.from_numpy(np.ascontiguousarray(idx_np, dtype=np.int64)).cuda()
+    if out is None:
+        out = torch.full((len(idx_np), table.dim), -7.0, dtype=TORCH_DT[dtype], device="cuda")
+    z.gather_ex(table, idx_dev, out, opts, n_idx=len(idx_np))
+    torch.cuda.synchronize()
+    return out
+
+
+def assert_same_bits(got_torch, want_np, what=""):
+    got = got_torch.cpu().numpy()
+    assert got.shape == want_np.shape, what
+    if got.tobytes() != want_np.tobytes():
+        bad = np.argwhere(got.view(np.uint8).reshape(got.shape[0], -1)
+                          != want_np.view(np.uint8).reshape(got.shape[0], -1))
+        raise AssertionError(f"{what}: {len(bad)} bytes differ, first at row/byte {bad[0]}")
+
+
+SHAPES = [
+    # (n_rows, dim, dtype): row bytes 400, 2408, 512, 64, 4, 12, 28, 2, 514, 2048, 4100, 6
+    (5000, 100, "f32"), (3000, 602, "f32"), (4096, 128, "f32"), (9000, 16, "f32"),
+    (777, 1, "f32"), (1001, 3, "f32"), (1500, 7, "f32"), (513, 1, "f16"), (2000, 257, "f16"),
+    (1200, 1024, "f16"), (900, 1025, "f32"), (1100, 3, "f16"),
+]
+
+
+@pytest.mark.parametrize("n_rows,dim,dtype", SHAPES)
+def test_all_variants_match_oracle(n_rows, dim, dtype):
+    table = host_table(n_rows, dim, dtype, seed=n_rows + dim)
+    try:
+        host = table.host_array()
+        for n_idx in (1, 63, 4099):
+            idx = wl.uniform_indices(n_idx, n_rows, seed=n_idx)
+            want = oracle_gather(host, idx)
+            for variant in ALL_VARIANTS:
+                got = run_gather(table, idx, dtype, z.LaunchOpts(variant=variant))
+                assert_same_bits(got, want, f"{dtype} dim={dim} n_idx={n_idx} variant={variant}")
+    finally:
+        table.close()
+
+
+@pytest.mark.parametrize("dim,dtype", [(100, "f32"), (602, "f32"), (257, "f16"), (2050, "f16")])
+def test_launch_knobs_do_not_change_the_result(dim, dtype):
+    n_rows = 3001
+    table = host_table(n_rows, dim, dtype, seed=dim)
+    try:
+        idx = wl.uniform_indices(10007, n_rows, seed=3)
+        want = oracle_gather(table.host_array(), idx)
+        for variant in (z.VARIANT_ROWVEC, z.VARIANT_ALIGNED):
+            for unroll in (1, 2, 4, 8):
+                for line in (32, 64, 128, 256):
+                    o = z.LaunchOpts(variant=variant, unroll=unroll, line_bytes=line)
+                    assert_same_bits(run_gather(table, idx, dtype, o), want, f"u{unroll} l{line}")
+            for vec in (2, 4, 8, 16):
+                if vec < table.elem_bytes:
+                    continue
+                o = z.LaunchOpts(variant=variant, vec_bytes=vec, nt_loads=1, nt_stores=2)
+                assert_same_bits(run_gather(table, idx, dtype, o), want, f"vec{vec}")
+            # one block only: the grid-stride loop does all the work
+            o = z.LaunchOpts(variant=variant, max_blocks=1)
+            assert_same_bits(run_gather(table, idx, dtype, o), want, "max_blocks=1")
+        o = z.LaunchOpts(variant=z.VARIANT_NAIVE, max_blocks=3, nt_loads=1)
+        assert_same_bits(run_gather(table, idx, dtype, o), want, "naive 3 blocks")
+    finally:
+        table.close()
+
+
+def test_raw_bit_patterns_and_invariants():
+    n_rows, dim = 2048, 100
+    table = host_table(n_rows, dim, "f32", seed=8, mode=wl.FILL_RAW_BITS)
+    try:
+        host = table.host_array()
+        # identity list reproduces the table, NaN payloads included
+        got = run_gather(table, np.arange(n_rows), "f32")
+        assert got.cpu().numpy().tobytes() == host.tobytes()
+        # duplicates give identical rows; permutation of the list permutes the rows
+        idx = wl.uniform_indices(5000, n_rows, seed=1)
+        perm = np.random.default_rng(0).permutation(5000)
+        a = run_gather(table, idx, "f32").cpu().numpy().view(np.uint32)
+        b = run_gather(table, idx[perm], "f32").cpu().numpy().view(np.uint32)
+        assert (a[perm] == b).all()
+        assert a.tobytes() == oracle_gather(host, idx).tobytes()
+    finally:
+        table.close()
+
+
+def test_empty_list_and_argument_errors():
+    table = host_table(100, 8, "f32", seed=1)
+    try:
+        out = torch.zeros((4, 8), dtype=torch.float32, device="cuda")
+        idx = torch.zeros(4, dtype=torch.int64, device="cuda")
+        z.gather(table, idx, out, n_idx=0)  # no launch, no error
+        with pytest.raises(z.ZcgError) as e:
+            z.gather(table, idx, out, n_idx=-1)
+        assert e.value.status == -1
+        with pytest.raises(z.ZcgError) as e:  # output inside the table
+            z.gather(table, idx, table.device_ptr + 64, n_idx=4)
+        assert e.value.status == -7
+        with pytest.raises(z.ZcgError) as e:  # output not aligned to the element
+            z.gather(table, idx, out.data_ptr() + 2, n_idx=2)
+        assert e.value.status == -6
+        with pytest.raises(z.ZcgError) as e:
+            z.gather_ex(table, idx, out, z.LaunchOpts(unroll=3), n_idx=4)
+        assert e.value.status == -1
+        with pytest.raises(TypeError):
+            z.gather(table, idx.to(torch.int32), out)
+        assert z.validate_indices(table, idx) == 0
+        bad = torch.tensor([0, 100, -1, 99, 1 << 40], dtype=torch.int64, device="cuda")
+        assert z.validate_indices(table, bad) == 3
+    finally:
+        table.close()
+    with pytest.raises(z.ZcgError) as e:  # dead handle
+        z.gather(table.__class__(12345, 100, 8, z.F32), idx, out, n_idx=4)
+    assert e.value.status == -3
+
+
+@pytest.mark.parametrize("byte_off", [4, 8, 16, 48, 100])
+def test_unaligned_bases(byte_off):
+    """Table base and output base off the 16 B / line grid: the kernels must pick
+    their access width and alignment from the real addresses."""
+    n_rows, dim = 2000, 100
+    table = host_table(n_rows + 1, dim, "f32", seed=5)
+    try:
+        host = table.host_array().reshape(-1)
+        sub = host[byte_off // 4: byte_off // 4 + n_rows * dim].reshape(n_rows, dim)
+        view = z.table_from_device(table.device_ptr + byte_off, n_rows, dim, "f32")
+        idx = wl.uniform_indices(3000, n_rows, seed=2)
+        want = oracle_gather(np.ascontiguousarray(sub), idx)
+        for variant in ALL_VARIANTS:
+            got = run_gather(view, idx, "f32", z.LaunchOpts(variant=variant))
+            assert_same_bits(got, want, f"table+{byte_off} variant={variant}")
+            # output base shifted as well
+            buf = torch.zeros(3000 * dim + 64, dtype=torch.float32, device="cuda")
+            o = buf[byte_off // 4: byte_off // 4 + 3000 * dim].view(3000, dim)
+            got = run_gather(view, idx, "f32", z.LaunchOpts(variant=variant), out=o)
+            assert_same_bits(got, want, f"out+{byte_off} variant={variant}")
+            assert float(buf[: byte_off // 4].abs().sum()) == 0.0  # nothing written before out
+            assert float(buf[byte_off // 4 + 3000 * dim:].abs().sum()) == 0.0  # nor after
+        view.close()
+    finally:
+        table.close()
+
+
+def test_hbm_resident_table_and_noncoherent_host_table():
+    n_rows, dim = 6000, 602
+    np_table = wl.make_table(n_rows, dim, "f32", seed=21)
+    idx = wl.uniform_indices(7001, n_rows, seed=6)
+    want = oracle_gather(np_table, idx)
+    dev = torch.from_numpy(np_table).cuda()
+    t = z.table_from_device(dev, n_rows, dim, "f32")
+    for variant in ALL_VARIANTS:
+        assert_same_bits(run_gather(t, idx, "f32", z.LaunchOpts(variant=variant)), want, "hbm")
+    t.close()
+    t = host_table(n_rows, dim, "f32", seed=21, flags=z.ALLOC_NONCOHERENT)
+    for variant in ALL_VARIANTS:
+        assert_same_bits(run_gather(t, idx, "f32", z.LaunchOpts(variant=variant)), want, "noncoh")
+    t.close()
+
+
+def test_cpu_gather_memcpy_baseline_matches_oracle():
+    n_rows, dim = 20000, 100
+    table = host_table(n_rows, dim, "f32", seed=4)
+    try:
+        idx = wl.uniform_indices(30011, n_rows, seed=9)
+        want = oracle_gather(table.host_array(), idx)
+        n_bytes = idx.size * table.row_bytes
+        staging = z.pinned_alloc(n_bytes)
+        for chunk in (0, 4096, 50000):
+            out = torch.zeros((idx.size, dim), dtype=torch.float32, device="cuda")
+            if chunk:
+                z.cpu_gather_memcpy_chunked(table, idx, staging, out, chunk, n_threads=4)
+            else:
+                z.cpu_gather_memcpy(table, idx, staging, out, n_threads=4)
+            torch.cuda.synchronize()
+            assert_same_bits(out, want, f"cpu baseline chunk={chunk}")
+        with pytest.raises(z.ZcgError) as e:
+            z.cpu_gather_memcpy(table, np.array([0, n_rows]), staging, out)
+        assert e.value.status == -8
+        z.pinned_free(staging)
+    finally:
+        table.close()
+
+
+def test_gather_on_a_side_stream():
+    n_rows, dim = 5000, 100
+    table = host_table(n_rows, dim, "f32", seed=2)
+    try:
+        idx = wl.uniform_indices(20000, n_rows, seed=1)
+        want = oracle_gather(table.host_array(), idx)
+        idx_dev = torch.from_numpy(idx).cuda()
+        out = torch.zeros((idx.size, dim), dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        s = torch.cuda.Stream()
+        z.gather(table, idx_dev, out, stream=s)
+        s.synchronize()
+        assert_same_bits(out, want, "side stream")
+    finally:
+        table.close()

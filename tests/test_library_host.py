@@ -1,0 +1,181 @@
+"""Host-side checks of libzcgather that need no GPU: the library loads, exports
+every symbol the header declares, rejects bad arguments before touching the
+GPU, and plans launches as documented."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2103_03330_amd as z
+from paper_2103_03330_amd.binding import EXPORTS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_header_and_library_agree_on_exports():
+    header = open(os.path.join(ROOT, "include", "zcgather.h")).read()
+    declared = set(re.findall(r"\b(zcg_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(EXPORTS)
+    lib = z.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert z.version() == "0.1"
+
+
+def test_status_strings():
+    for code in range(0, -9, -1):
+        assert z.strerror(code) != "unknown status"
+    assert z.strerror(-99) == "unknown status"
+
+
+def test_argument_checks_run_before_any_gpu_call():
+    a = np.zeros((4, 4), np.float32)
+    cases = [
+        (lambda: z.register_table(0, 4, 4, "f32"), z.binding.EINVAL),
+        (lambda: z.register_table(a, 0, 4, "f32"), z.binding.EINVAL),
+        (lambda: z.register_table(a, 4, -1, "f32"), z.binding.EINVAL),
+        (lambda: z.register_table(a, 4, 4, 7), z.binding.EDTYPE),
+        (lambda: z.register_table(a.ctypes.data + 2, 4, 3, "f32"), z.binding.EALIGN),
+        (lambda: z.alloc_table(4, 4, "f32", flags=64), z.binding.EINVAL),
+        (lambda: z.alloc_table(2 ** 62, 2 ** 10, "f32"), z.binding.EINVAL),
+        (lambda: z.table_from_device(0, 4, 4, "f32"), z.binding.EINVAL),
+        (lambda: z.table_from_device(4098, 4, 4, "f32"), z.binding.EALIGN),
+        (lambda: z.measure_h2d(0), z.binding.EINVAL),
+        (lambda: z.pinned_alloc(-5), z.binding.EINVAL),
+    ]
+    for fn, want in cases:
+        with pytest.raises(z.ZcgError) as e:
+            fn()
+        assert e.value.status == want
+
+
+def test_handles_die_once():
+    t = z.table_from_device(0x10000, 10, 4, "f32")
+    assert t.device_ptr == 0x10000 and t.host_ptr == 0 and t.row_bytes == 16
+    h = t.handle
+    t.close()
+    t.close()  # idempotent on the Python object
+    lib = z.load_library()
+    assert lib.zcg_unregister_table(h) == z.binding.EHANDLE  # the C handle is dead
+    assert lib.zcg_unregister_table(None) == z.binding.EHANDLE
+    assert lib.zcg_table_device_ptr(h) is None
+    assert lib.zcg_gather(h, 8, 1, 16, None) == z.binding.EHANDLE
+
+
+def test_gather_rejects_before_launch():
+    t = z.table_from_device(0x100000, 100, 25, "f32")  # 100-byte rows at 0x100000
+    lib = z.load_library()
+    try:
+        assert lib.zcg_gather(t.handle, None, 0, None, None) == 0  # empty list: nothing to do
+        assert lib.zcg_gather(t.handle, None, 5, 0x900000, None) == z.binding.EINVAL
+        assert lib.zcg_gather(t.handle, 0x800000, -1, 0x900000, None) == z.binding.EINVAL
+        assert lib.zcg_gather(t.handle, 0x800004, 5, 0x900000, None) == z.binding.EALIGN
+        assert lib.zcg_gather(t.handle, 0x800000, 5, 0x900002, None) == z.binding.EALIGN
+        # output overlapping the table's [0x100000, 0x100000 + 10000)
+        assert lib.zcg_gather(t.handle, 0x800000, 5, 0x100000 + 9996, None) == z.binding.EALIAS
+        assert lib.zcg_gather(t.handle, 0x800000, 5, 0x100000 - 400, None) == z.binding.EALIAS
+        assert lib.zcg_gather_variant(t.handle, 0x800000, 5, 0x900000, None, 9) == z.binding.EINVAL
+    finally:
+        t.close()
+
+
+def test_cpu_baseline_rejects_device_tables_and_bad_lists():
+    t = z.table_from_device(0x100000, 100, 25, "f32")
+    try:
+        with pytest.raises(z.ZcgError) as e:
+            z.cpu_gather_memcpy(t, np.array([1, 2]), 0x1000, 0x2000)
+        assert e.value.status == z.binding.EINVAL
+    finally:
+        t.close()
+
+
+def plan(row_elems, dtype, table_addr=0x7F0000000000, out_addr=0x7E0000000000, n_idx=100000, **kw):
+    t = z.table_from_device(table_addr, 1000, row_elems, dtype)
+    try:
+        return z.plan_gather(t, n_idx, out_addr, z.LaunchOpts(**kw) if kw else None)
+    finally:
+        t.close()
+
+
+def test_plan_picks_width_group_and_variant():
+    p = plan(100, "f32")  # 400-byte rows: unaligned to 128 -> ALIGNED, 16-byte lanes
+    assert (p["variant"], p["vec_bytes"], p["log2_group"], p["iters"]) == (z.VARIANT_ALIGNED, 16, 5, 1)
+    p = plan(602, "f32")  # 2,408-byte rows: 8-byte lanes, a wave per row, several passes
+    assert (p["variant"], p["vec_bytes"], p["log2_group"]) == (z.VARIANT_ALIGNED, 8, 6)
+    assert p["iters"] == -(-(2408 + 120) // 512)
+    p = plan(128, "f32")  # whole lines on an aligned base: no realignment needed
+    assert (p["variant"], p["vec_bytes"], p["log2_group"], p["iters"]) == (z.VARIANT_ROWVEC, 16, 5, 1)
+    p = plan(16, "f16")  # 32-byte rows, shorter than a line
+    assert (p["variant"], p["vec_bytes"], p["log2_group"]) == (z.VARIANT_ROWVEC, 16, 1)
+    p = plan(128, "f32", table_addr=0x7F0000000040)  # same rows on a base 64 bytes off the line
+    assert p["variant"] == z.VARIANT_ALIGNED
+    p = plan(100, "f32", table_addr=0x7F0000000004)  # base only element-aligned
+    assert p["vec_bytes"] == 4
+    p = plan(100, "f32", out_addr=0x7E0000000008)
+    assert p["vec_bytes"] == 8
+    p = plan(3, "f16")
+    assert p["vec_bytes"] == 2
+    p = plan(100, "f32", variant=z.VARIANT_NAIVE)
+    assert (p["variant"], p["vec_bytes"]) == (z.VARIANT_NAIVE, 4)
+    p = plan(100, "f32", max_blocks=7)
+    assert p["blocks"] == 7
+    p = plan(100, "f32", n_idx=3)
+    assert p["blocks"] == 1
+    for bad in (dict(unroll=3), dict(line_bytes=48), dict(vec_bytes=2), dict(variant=4),
+                dict(nt_loads=3)):
+        with pytest.raises(z.ZcgError):
+            plan(100, "f32", **bad)
+
+
+def covered_bytes(row_bytes, src_addr, p):
+    """Replays the row kernels' lane->chunk mapping for one row on the host:
+    returns the sorted list of (source byte, destination byte offset in row)."""
+    w, line = p["vec_bytes"], p["line_bytes"]
+    mask = (line - 1) if p["variant"] == z.VARIANT_ALIGNED else 0
+    mis = src_addr & mask
+    g = 1 << p["log2_group"]
+    pairs = []
+    for it in range(p["iters"]):
+        for lane in range(g):
+            off = (it * g + lane) * w - mis
+            if 0 <= off < row_bytes:
+                pairs.extend((src_addr + off + b, off + b) for b in range(w))
+    return sorted(pairs)
+
+
+@pytest.mark.parametrize("row_elems,dtype", [(100, "f32"), (602, "f32"), (120, "f32"), (257, "f16"),
+                                             (1025, "f32"), (16, "f16"), (3, "f32")])
+def test_lane_mapping_covers_each_row_byte_exactly_once(row_elems, dtype):
+    elem = 2 if dtype == "f16" else 4
+    rb = row_elems * elem
+    base = 0x7F0000000000
+    for variant in (z.VARIANT_ROWVEC, z.VARIANT_ALIGNED):
+        for line in (64, 128):
+            p = plan(row_elems, dtype, table_addr=base, variant=variant, line_bytes=line)
+            for row in (0, 1, 2, 5, 77):
+                src = base + row * rb
+                got = covered_bytes(rb, src, p)
+                assert got == [(src + b, b) for b in range(rb)]
+
+
+def test_aligned_loads_touch_each_line_once(golden):
+    """The paper's worked example on this kernel's mapping: the second 480-byte row
+    costs 5 line requests when wave loads start on line boundaries, 8 when a
+    32-lane, 4-byte-per-lane group starts at the row start."""
+    rb, line = golden["example_row_bytes"], golden["example_line_bytes"]
+    src = rb * golden["example_source_row"]
+
+    def requests(mis, w, g):
+        seen = set()
+        n_chunks = -(-(mis + rb) // w)
+        for c in range(n_chunks):
+            off = c * w - mis
+            if 0 <= off < rb:
+                seen.add((c // g, (src + off) // line))
+        return len(seen)
+
+    assert requests(0, 4, 32) == golden["example_requests_naive"]
+    assert requests(src % line, 4, 32) == golden["example_requests_shifted"]
+    assert requests(src % line, 16, 64) == golden["example_requests_shifted"]
