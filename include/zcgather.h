@@ -49,9 +49,12 @@ extern "C" {
                                     lines; host writes made while a kernel runs are
                                     not guaranteed visible to it                      */
 #define ZCG_ALLOC_NUMA_USER 2u   /* keep the calling thread's NUMA policy           */
+#define ZCG_ALLOC_UNCACHED 4u    /* pinned, mapped, extended fine-grained pool: the
+                                    GPU does not cache the table at all               */
 
 /* ---- gather kernels (zcg_gather_variant / zcg_gather_ex) --------------- */
-#define ZCG_VARIANT_AUTO 0    /* ALIGNED when rows are unaligned to the line, else ROWVEC */
+#define ZCG_VARIANT_AUTO 0    /* host table with partial row ends: HALFLINE; whole-line
+                                 rows: ROWVEC; HBM-resident table: ALIGNED / ROWVEC     */
 #define ZCG_VARIANT_NAIVE 1   /* one element per lane over the flat output, no alignment
                                  care: the paper's baseline kernel (Section 4.1.2 (c))  */
 #define ZCG_VARIANT_ROWVEC 2  /* a lane group per row, widest vector, loads start at the
@@ -61,7 +64,12 @@ extern "C" {
                                  wave load covers whole lines: the goal of the paper's
                                  circular shift (Section 3.2.1), reads aligned, the
                                  misalignment moved to the local writes                */
-#define ZCG_VARIANT_COUNT 4
+#define ZCG_VARIANT_HALFLINE 4 /* ALIGNED, and row ends that occupy at most half a line are
+                                  fetched as 64-byte reads through the scalar data cache:
+                                  on gfx950 a vector load of host memory always costs the
+                                  whole 128-byte line on the link, a scalar load half of
+                                  it. Needs 4-byte-aligned rows and bases, else ALIGNED. */
+#define ZCG_VARIANT_COUNT 5
 
 typedef struct zcg_table zcg_table; /* opaque */
 
@@ -71,20 +79,22 @@ typedef struct zcg_launch_opts {
   int max_blocks;  /* cap on the grid size (blocks of 256 lanes); the kernels stride   */
   int unroll;      /* independent loads in flight per lane: 1, 2, 4 or 8               */
   int line_bytes;  /* alignment target of ALIGNED: 32, 64, 128 or 256                  */
-  int nt_loads;    /* 1: non-temporal table loads, 2: plain loads                      */
+  int nt_loads;    /* 1: non-temporal table loads, 2: plain loads, 3: system scope     */
   int nt_stores;   /* 1: non-temporal output stores, 2: plain stores                   */
   int vec_bytes;   /* cap on bytes per lane access: 2, 4, 8 or 16                      */
+  int group_lanes; /* lanes given to one row, a power of two up to 64; raised to what
+                      the row needs. 64 = one row per wave-wide load instruction       */
 } zcg_launch_opts;
 
 /* How one gather call is laid out on the GPU; filled by zcg_plan_gather. */
 typedef struct zcg_plan {
-  int variant;     /* resolved: NAIVE, ROWVEC or ALIGNED                               */
+  int variant;     /* resolved: NAIVE, ROWVEC, ALIGNED or HALFLINE                     */
   int vec_bytes;   /* bytes per lane access                                            */
   int log2_group;  /* lanes per row = 1 << log2_group (row kernels)                    */
   int iters;       /* group-wide passes needed to cover the widest (aligned) row span  */
   int unroll;      /* independent loads in flight per lane                             */
   int line_bytes;  /* alignment target (ALIGNED)                                       */
-  int nt_loads;    /* 0 / 1                                                            */
+  int nt_loads;    /* 0 plain, 1 non-temporal, 2 system scope                          */
   int nt_stores;   /* 0 / 1                                                            */
   int blocks;      /* grid size, blocks of 256 lanes                                   */
 } zcg_plan;

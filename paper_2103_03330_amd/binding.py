@@ -21,10 +21,10 @@ from . import build as _build
 # status codes / constants (include/zcgather.h)
 OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE = 0, -1, -2, -3, -4, -5, -6, -7, -8
 F16, F32 = 1, 2
-ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER = 0, 1, 2
-VARIANT_AUTO, VARIANT_NAIVE, VARIANT_ROWVEC, VARIANT_ALIGNED = 0, 1, 2, 3
+ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER, ALLOC_UNCACHED = 0, 1, 2, 4
+VARIANT_AUTO, VARIANT_NAIVE, VARIANT_ROWVEC, VARIANT_ALIGNED, VARIANT_HALFLINE = 0, 1, 2, 3, 4
 VARIANT_NAMES = {VARIANT_AUTO: "auto", VARIANT_NAIVE: "naive", VARIANT_ROWVEC: "rowvec",
-                 VARIANT_ALIGNED: "aligned"}
+                 VARIANT_ALIGNED: "aligned", VARIANT_HALFLINE: "halfline"}
 _DTYPES = {"f16": F16, "f32": F32, F16: F16, F32: F32}
 _ELEM = {F16: 2, F32: 4}
 _NP = {F16: np.float16, F32: np.float32}
@@ -43,7 +43,8 @@ class LaunchOpts(ctypes.Structure):
     """zcg_launch_opts; zero in a field means the library default."""
     _fields_ = [("variant", ctypes.c_int), ("max_blocks", ctypes.c_int), ("unroll", ctypes.c_int),
                 ("line_bytes", ctypes.c_int), ("nt_loads", ctypes.c_int),
-                ("nt_stores", ctypes.c_int), ("vec_bytes", ctypes.c_int)]
+                ("nt_stores", ctypes.c_int), ("vec_bytes", ctypes.c_int),
+                ("group_lanes", ctypes.c_int)]
 
 
 class Plan(ctypes.Structure):

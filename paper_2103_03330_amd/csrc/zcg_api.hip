@@ -126,11 +126,13 @@ int zcg_alloc_table(int64_t n_rows, int64_t dim, int dtype, unsigned flags, int 
   int elem;
   int rc = check_shape(n_rows, dim, dtype, out, &elem);
   if (rc) return rc;
-  if (device < 0 || (flags & ~(ZCG_ALLOC_NONCOHERENT | ZCG_ALLOC_NUMA_USER))) return ZCG_EINVAL;
+  if (device < 0 || (flags & ~(ZCG_ALLOC_NONCOHERENT | ZCG_ALLOC_NUMA_USER | ZCG_ALLOC_UNCACHED))) return ZCG_EINVAL;
   DeviceScope scope(device);
   if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
   unsigned hip_flags = hipHostMallocMapped | hipHostMallocPortable;
-  hip_flags |= (flags & ZCG_ALLOC_NONCOHERENT) ? hipHostMallocNonCoherent : hipHostMallocCoherent;
+  if ((flags & ZCG_ALLOC_NONCOHERENT) && (flags & ZCG_ALLOC_UNCACHED)) return ZCG_EINVAL;
+  if (flags & ZCG_ALLOC_UNCACHED) hip_flags |= hipHostMallocUncached;
+  else hip_flags |= (flags & ZCG_ALLOC_NONCOHERENT) ? hipHostMallocNonCoherent : hipHostMallocCoherent;
   if (flags & ZCG_ALLOC_NUMA_USER) hip_flags |= hipHostMallocNumaUser;
   void* host = nullptr;
   hipError_t e = hipHostMalloc(&host, (size_t)(n_rows * dim * elem), hip_flags);

@@ -25,10 +25,14 @@ template <> struct vec_of<8> { typedef u32x2 type; };
 template <> struct vec_of<4> { typedef uint32_t type; };
 template <> struct vec_of<2> { typedef uint16_t type; };
 
-template <int W, bool NT>
+// Load modes: 0 plain, 1 non-temporal (nt), 2 system scope (sc0 sc1).
+template <int W, int LM>
 __device__ __forceinline__ typename vec_of<W>::type load_chunk(const uint8_t* p) {
-  const auto* q = reinterpret_cast<const typename vec_of<W>::type*>(p);
-  if constexpr (NT) return __builtin_nontemporal_load(q);
+  typedef typename vec_of<W>::type vec;
+  const auto* q = reinterpret_cast<const vec*>(p);
+  if constexpr (LM == 1) return __builtin_nontemporal_load(q);
+  else if constexpr (LM == 2)
+    return *(const volatile vec __attribute__((address_space(1)))*)(q);
   else return *q;
 }
 
@@ -43,7 +47,7 @@ __device__ __forceinline__ void store_chunk(uint8_t* p, typename vec_of<W>::type
 // device-resident dummy: the load stays unconditional (so the compiler can keep
 // U of them in flight without merging values across branches) and no byte
 // outside the row is ever requested from the table.
-__device__ __align__(16) uint32_t zcg_dummy_chunk[4];
+__device__ __align__(64) uint32_t zcg_dummy_chunk[16];
 
 // Rows whose (aligned) span fits one pass of a lane group of 1 << log2_g lanes.
 // Lane l of the group owns the W-byte chunk at  floor(row_start, line) + l*W
@@ -51,7 +55,7 @@ __device__ __align__(16) uint32_t zcg_dummy_chunk[4];
 // lines of the source except at the two row ends. With line_mask == 0 the
 // chunks start at the row start instead. Each group keeps U rows in flight:
 // U index loads, then U table loads, then U stores.
-template <int W, int U, bool NTL, bool NTS>
+template <int W, int U, int NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_narrow(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
                   int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g,
@@ -89,7 +93,7 @@ zcg_k_rows_narrow(const uint8_t* __restrict__ table, const int64_t* __restrict__
 
 // Rows wider than one wave pass: one wavefront per row, walking the aligned
 // span in steps of 64*W bytes, U steps in flight.
-template <int W, int U, bool NTL, bool NTS>
+template <int W, int U, int NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_wide(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx, int64_t n_idx,
                 uint8_t* __restrict__ out, int64_t row_bytes, unsigned line_mask) {
@@ -122,9 +126,169 @@ zcg_k_rows_wide(const uint8_t* __restrict__ table, const int64_t* __restrict__ i
   }
 }
 
+// ---------------------------------------------------------------------------
+// HALFLINE kernels.
+//
+// Measured on gfx950: a vector load of mapped host memory always costs whole
+// 128-byte lines on the host link, whatever part of the line the wave asks
+// for; a load through the scalar data cache costs one 64-byte half line. So a
+// row end that occupies at most one half of its line is fetched with a
+// wave-uniform 64-byte scalar load (16 SGPRs, then 16 lanes store one dword
+// each), and only the rest of the row with whole-line vector loads:
+//   head piece: row start S with S mod 128 >= 64  -> bytes [S, next line)
+//   tail piece: row end E with (E-1) mod 128 < 64 -> bytes [line of E-1, E)
+// A 400-byte row then moves 3 lines + 1 half line (448 bytes) instead of 4
+// lines (512 bytes). This is the paper's aim (Section 3.2.1: as few and as full
+// link requests as possible for unaligned rows) with this chip's own means.
+// Requires 4-byte-aligned rows, table and output. The scalar cache is
+// invalidated at kernel start like the other caches, never written.
+// ---------------------------------------------------------------------------
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+typedef const u32x16 __attribute__((address_space(4)))* half_line_ptr;
+
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t x, int src_lane) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, src_lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(x >> 32), src_lane);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// Where one row's bytes come from. All fields are byte addresses in the table.
+struct RowSplit {
+  uint64_t vs, ve;           // [vs, ve): moved by vector loads (whole lines except at S / E)
+  uint64_t head_addr;        // 64-byte aligned source of the head piece (valid if has_head)
+  uint64_t tail_addr;        // 64-byte aligned source of the tail piece (valid if has_tail)
+  bool has_head, has_tail;
+};
+
+__device__ __forceinline__ RowSplit split_row(uint64_t S, uint64_t row_bytes) {
+  RowSplit p;
+  const uint64_t E = S + row_bytes;
+  p.has_head = (S & 127u) >= 64u;
+  const uint64_t next_line = (S | 127u) + 1u;
+  p.vs = p.has_head ? (E < next_line ? E : next_line) : S;
+  p.head_addr = S & ~(uint64_t)63u;
+  const uint64_t last_line = (E - 1u) & ~(uint64_t)127u;
+  p.has_tail = (p.vs < E) && (((E - 1u) & 127u) < 64u);
+  p.tail_addr = last_line;
+  p.ve = p.has_tail ? (p.vs > last_line ? p.vs : last_line) : E;
+  return p;
+}
+
+// Moves the head / tail pieces of one row (wave-uniform S, r). Lanes 0-15 carry
+// the head piece's 16 dwords, lanes 16-31 the tail piece's.
+__device__ __forceinline__ void move_pieces(const RowSplit& sp, uint64_t S, uint64_t row_bytes,
+                                            uint8_t* __restrict__ out_row, unsigned wave_lane) {
+  const uint64_t dummy = (uint64_t)(uintptr_t)zcg_dummy_chunk;
+  const u32x16 hv = *(half_line_ptr)(sp.has_head ? sp.head_addr : dummy);
+  const u32x16 tv = *(half_line_ptr)(sp.has_tail ? sp.tail_addr : dummy);
+  const unsigned k = wave_lane & 15u;
+  uint32_t h = 0, t = 0;
+#pragma unroll
+  for (unsigned j = 0; j < 16; ++j) {
+    h = (k == j) ? hv[j] : h;
+    t = (k == j) ? tv[j] : t;
+  }
+  const bool is_head_lane = wave_lane < 16u;
+  const uint64_t a = (is_head_lane ? sp.head_addr : sp.tail_addr) + 4u * k;  // source of my dword
+  const uint64_t lo = is_head_lane ? S : sp.ve;
+  const uint64_t hi = is_head_lane ? sp.vs : S + row_bytes;
+  const bool mine = wave_lane < 32u && (is_head_lane ? sp.has_head : sp.has_tail) && a >= lo && a < hi;
+  if (mine) *reinterpret_cast<uint32_t*>(out_row + (a - S)) = is_head_lane ? h : t;
+}
+
+template <int W, int U, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
+                       int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g) {
+  typedef typename vec_of<W>::type vec;
+  const unsigned wave_lane = threadIdx.x & (kWave - 1);
+  const unsigned lane = threadIdx.x & ((1u << log2_g) - 1u);
+  const int groups_per_wave = kWave >> log2_g;
+  const int64_t n_groups = ((int64_t)gridDim.x * kBlock) >> log2_g;
+  const int64_t wave_group0 = ((int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1))) >> log2_g;
+  const int my_group = (int)(wave_lane >> log2_g);
+  const int64_t lane_off = (int64_t)lane * W;
+  const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
+
+  // wave-uniform trip count: the wave's first group decides
+  for (int64_t wbase = wave_group0; wbase < n_idx; wbase += n_groups * U) {
+    int64_t row_id[U];
+    uint64_t src[U];
+    vec v[U];
+    int64_t dst[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = wbase + my_group + (int64_t)u * n_groups;
+      row_id[u] = idx[r < n_idx ? r : n_idx - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = wbase + my_group + (int64_t)u * n_groups;
+      const uint64_t S = (uint64_t)(uintptr_t)(table + row_id[u] * row_bytes);
+      src[u] = S;
+      const RowSplit sp = split_row(S, (uint64_t)row_bytes);
+      const uint64_t a = (S & ~(uint64_t)127u) + (uint64_t)lane_off;  // line-aligned lane mapping
+      const bool ok = (r < n_idx) && (a >= sp.vs) && (a < sp.ve);
+      // pointer formed from `table` so that the load stays a global (not flat) access
+      v[u] = load_chunk<W, 0>(ok ? table + (a - (uint64_t)(uintptr_t)table) : dummy);
+      dst[u] = ok ? r * row_bytes + (int64_t)(a - S) : -1;
+    }
+    // row ends through the scalar cache, one row of the wave at a time
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      for (int g = 0; g < groups_per_wave; ++g) {
+        const int64_t r = wbase + g + (int64_t)u * n_groups;  // uniform
+        if (r < n_idx) {
+          const uint64_t S = uniform_u64(src[u], g << log2_g);
+          const RowSplit sp = split_row(S, (uint64_t)row_bytes);
+          if (sp.has_head || sp.has_tail)
+            move_pieces(sp, S, (uint64_t)row_bytes, out + r * row_bytes, wave_lane);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (dst[u] >= 0) store_chunk<W, NTS>(out + dst[u], v[u]);
+  }
+}
+
+template <int W, int U, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
+                     int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes) {
+  typedef typename vec_of<W>::type vec;
+  const unsigned lane = threadIdx.x & (kWave - 1);
+  const int64_t n_waves = ((int64_t)gridDim.x * kBlock) / kWave;
+  const int64_t wave = ((int64_t)blockIdx.x * kBlock + (threadIdx.x & ~(kWave - 1))) / kWave;
+  constexpr int64_t kStep = (int64_t)kWave * W;
+  const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
+
+  for (int64_t r = wave; r < n_idx; r += n_waves) {
+    const uint64_t S = uniform_u64((uint64_t)(uintptr_t)(table + idx[r] * row_bytes), 0);
+    const RowSplit sp = split_row(S, (uint64_t)row_bytes);
+    uint8_t* out_row = out + r * row_bytes;
+    if (sp.has_head || sp.has_tail) move_pieces(sp, S, (uint64_t)row_bytes, out_row, lane);
+    const uint64_t a0 = (sp.vs & ~(uint64_t)127u) + (uint64_t)lane * W;  // line-aligned lane mapping
+    for (uint64_t a = a0; a < sp.ve; a += kStep * U) {
+      vec v[U];
+      bool ok[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t au = a + (uint64_t)u * kStep;
+        ok[u] = (au >= sp.vs) && (au < sp.ve);
+        v[u] = load_chunk<W, 0>(ok[u] ? table + (au - (uint64_t)(uintptr_t)table) : dummy);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) store_chunk<W, NTS>(out_row + (a + (uint64_t)u * kStep - S), v[u]);
+    }
+  }
+}
+
+
 // The baseline mapping: lane i of the flat grid copies element i of the dense
 // output, whatever row it falls in and wherever that row starts in the source.
-template <typename E, typename I, bool NTL, bool NTS>
+template <typename E, typename I, int NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_flat(const E* __restrict__ table, const int64_t* __restrict__ idx, int64_t n_idx,
            E* __restrict__ out, int64_t dim) {
@@ -136,7 +300,9 @@ zcg_k_flat(const E* __restrict__ table, const int64_t* __restrict__ idx, int64_t
     const I c = i - r * d;
     const E* s = table + idx[r] * dim + (int64_t)c;
     E v;
-    if constexpr (NTL) v = __builtin_nontemporal_load(s); else v = *s;
+    if constexpr (NTL == 1) v = __builtin_nontemporal_load(s);
+    else if constexpr (NTL == 2) v = *(const volatile E __attribute__((address_space(1)))*)(s);
+    else v = *s;
     if constexpr (NTS) __builtin_nontemporal_store(v, out + (int64_t)i); else out[(int64_t)i] = v;
   }
 }
@@ -164,6 +330,24 @@ hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* i
                        uint8_t* out, int64_t row_bytes, hipStream_t s) {
   const unsigned mask = (p.variant == ZCG_VARIANT_ALIGNED) ? (unsigned)(p.line_bytes - 1) : 0u;
   const dim3 grid((unsigned)p.blocks), block(kBlock);
+  if constexpr (W >= 4) {
+    if (p.variant == ZCG_VARIANT_HALFLINE) {
+      if (p.iters == 1) {
+        if (p.nt_stores)
+          zcg_k_rows_narrow_half<W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                     row_bytes, p.log2_group);
+        else
+          zcg_k_rows_narrow_half<W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                      row_bytes, p.log2_group);
+      } else {
+        if (p.nt_stores)
+          zcg_k_rows_wide_half<W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes);
+        else
+          zcg_k_rows_wide_half<W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes);
+      }
+      return hipGetLastError();
+    }
+  }
 #define ZCG_LAUNCH(NTL, NTS)                                                                    \
   do {                                                                                          \
     if (p.iters == 1)                                                                           \
@@ -173,10 +357,14 @@ hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* i
       zcg_k_rows_wide<W, U, NTL, NTS><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes, \
                                                                mask);                           \
   } while (0)
-  if (p.nt_loads && p.nt_stores) ZCG_LAUNCH(true, true);
-  else if (p.nt_loads) ZCG_LAUNCH(true, false);
-  else if (p.nt_stores) ZCG_LAUNCH(false, true);
-  else ZCG_LAUNCH(false, false);
+  switch (p.nt_loads * 2 + (p.nt_stores ? 1 : 0)) {
+    case 0: ZCG_LAUNCH(0, false); break;
+    case 1: ZCG_LAUNCH(0, true); break;
+    case 2: ZCG_LAUNCH(1, false); break;
+    case 3: ZCG_LAUNCH(1, true); break;
+    case 4: ZCG_LAUNCH(2, false); break;
+    default: ZCG_LAUNCH(2, true); break;
+  }
 #undef ZCG_LAUNCH
   return hipGetLastError();
 }
@@ -205,10 +393,14 @@ hipError_t launch_flat(const zcg_plan& p, const void* table, const int64_t* idx,
     if (small) zcg_k_flat<E, uint32_t, NTL, NTS><<<grid, block, 0, s>>>(t, idx, n_idx, o, dim); \
     else zcg_k_flat<E, int64_t, NTL, NTS><<<grid, block, 0, s>>>(t, idx, n_idx, o, dim);   \
   } while (0)
-  if (p.nt_loads && p.nt_stores) ZCG_LAUNCH(true, true);
-  else if (p.nt_loads) ZCG_LAUNCH(true, false);
-  else if (p.nt_stores) ZCG_LAUNCH(false, true);
-  else ZCG_LAUNCH(false, false);
+  switch (p.nt_loads * 2 + (p.nt_stores ? 1 : 0)) {
+    case 0: ZCG_LAUNCH(0, false); break;
+    case 1: ZCG_LAUNCH(0, true); break;
+    case 2: ZCG_LAUNCH(1, false); break;
+    case 3: ZCG_LAUNCH(1, true); break;
+    case 4: ZCG_LAUNCH(2, false); break;
+    default: ZCG_LAUNCH(2, true); break;
+  }
 #undef ZCG_LAUNCH
   return hipGetLastError();
 }
@@ -226,27 +418,51 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   // defaults
   int variant = o.variant;
   int line = o.line_bytes ? o.line_bytes : 128;
-  int unroll = o.unroll ? o.unroll : 4;
+  int unroll = o.unroll ? o.unroll : (host_resident ? 2 : 4);
   int vec_cap = o.vec_bytes ? o.vec_bytes : 16;
+  if (!o.vec_bytes && host_resident) {
+    // Measured over the host link: a row spread over (nearly) all 64 lanes of one
+    // load instruction is slightly faster than the same row in 16-byte chunks on
+    // fewer lanes, so prefer the narrowest chunk that still fits one wave pass.
+    int pref = 4;
+    while (pref < 16 && (int64_t)pref * kWave < row_bytes) pref <<= 1;
+    vec_cap = pref < elem ? elem : pref;
+  }
   int max_blocks = o.max_blocks ? o.max_blocks : (host_resident ? 2048 : 8192);
-  const int ntl = o.nt_loads == 1 ? 1 : 0;                 // default: plain loads
+  const int ntl = o.nt_loads == 1 ? 1 : (o.nt_loads == 3 ? 2 : 0);  // default: plain loads
   const int nts = o.nt_stores == 2 ? 0 : 1;                // default: non-temporal stores
   if (variant < 0 || variant >= ZCG_VARIANT_COUNT) return ZCG_EINVAL;
   if (line != 32 && line != 64 && line != 128 && line != 256) return ZCG_EINVAL;
   if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return ZCG_EINVAL;
   if (vec_cap != 2 && vec_cap != 4 && vec_cap != 8 && vec_cap != 16) return ZCG_EINVAL;
-  if (max_blocks < 1 || o.nt_loads < 0 || o.nt_loads > 2 || o.nt_stores < 0 || o.nt_stores > 2)
+  if (max_blocks < 1 || o.nt_loads < 0 || o.nt_loads > 3 || o.nt_stores < 0 || o.nt_stores > 2)
     return ZCG_EINVAL;
   if (vec_cap < elem) return ZCG_EINVAL;
+  int min_lg = 0;
+  if (o.group_lanes) {
+    if (o.group_lanes < 1 || o.group_lanes > kWave || (o.group_lanes & (o.group_lanes - 1)))
+      return ZCG_EINVAL;
+    while ((1 << min_lg) < o.group_lanes) ++min_lg;
+  } else if (host_resident) {
+    // Measured: over the host link one row per wave-wide load instruction is the
+    // fastest and the least sensitive to grid size and unrolling.
+    min_lg = 6;
+  }
 
   // Widest access that keeps every chunk of every row aligned at both ends.
   int w = floor_pow2_divisor((uint64_t)row_bytes, vec_cap);
   w = floor_pow2_divisor((uint64_t)table_addr, w);
   w = floor_pow2_divisor((uint64_t)out_addr, w);
 
+  // HALFLINE moves dwords through the scalar path: needs 4-byte granularity everywhere.
+  const bool half_ok = (w >= 4);
+  if (variant == ZCG_VARIANT_HALFLINE && !half_ok) variant = ZCG_VARIANT_ALIGNED;
+  if (variant == ZCG_VARIANT_HALFLINE) line = 128;
   if (variant == ZCG_VARIANT_AUTO) {
     // Rows shorter than a line, or made of whole lines on a line-aligned base,
     // need no realignment (the paper's applicability rule, end of Section 3.2.1).
+    // HALFLINE is never chosen here: it lowers the bytes on the link but not the
+    // time (the link side serves requests at a fixed rate, half lines included).
     const bool whole_lines = (row_bytes % line == 0) && (table_addr % (uintptr_t)line == 0);
     variant = (row_bytes < line || whole_lines) ? ZCG_VARIANT_ROWVEC : ZCG_VARIANT_ALIGNED;
   }
@@ -267,10 +483,12 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     want_blocks = (total + kBlock - 1) / kBlock;
   } else {
     plan->vec_bytes = w;
-    const int64_t worst_span = row_bytes + (variant == ZCG_VARIANT_ALIGNED ? line - w : 0);
+    const bool line_mapped = variant == ZCG_VARIANT_ALIGNED || variant == ZCG_VARIANT_HALFLINE;
+    const int64_t worst_span = row_bytes + (line_mapped ? line - w : 0);
     const int64_t chunks = (worst_span + w - 1) / w;
     int lg = 0;
     while (lg < 6 && ((int64_t)1 << lg) < chunks) ++lg;
+    if (lg < min_lg) lg = min_lg;
     plan->log2_group = lg;
     plan->iters = (int)((chunks + ((int64_t)1 << lg) - 1) >> lg);
     if (plan->iters == 1) {

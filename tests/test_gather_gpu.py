@@ -11,7 +11,8 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 z = pytest.importorskip("paper_2103_03330_amd")
 
-ALL_VARIANTS = [z.VARIANT_AUTO, z.VARIANT_NAIVE, z.VARIANT_ROWVEC, z.VARIANT_ALIGNED]
+ALL_VARIANTS = [z.VARIANT_AUTO, z.VARIANT_NAIVE, z.VARIANT_ROWVEC, z.VARIANT_ALIGNED,
+                z.VARIANT_HALFLINE]
 TORCH_DT = {"f16": torch.float16, "f32": torch.float32}
 
 
@@ -52,6 +53,9 @@ SHAPES = [
     (5000, 100, "f32"), (3000, 602, "f32"), (4096, 128, "f32"), (9000, 16, "f32"),
     (777, 1, "f32"), (1001, 3, "f32"), (1500, 7, "f32"), (513, 1, "f16"), (2000, 257, "f16"),
     (1200, 1024, "f16"), (900, 1025, "f32"), (1100, 3, "f16"),
+    # rows inside one half line (32 B, 64 B), straddling halves (48 B, 80 B, 200 B), 2-byte odd
+    (4000, 16, "f16"), (4000, 16, "f32"), (3000, 12, "f32"), (3000, 20, "f32"), (2500, 50, "f32"),
+    (2500, 98, "f16"), (1300, 99, "f16"), (700, 1023, "f32"),
 ]
 
 
@@ -77,7 +81,7 @@ def test_launch_knobs_do_not_change_the_result(dim, dtype):
     try:
         idx = wl.uniform_indices(10007, n_rows, seed=3)
         want = oracle_gather(table.host_array(), idx)
-        for variant in (z.VARIANT_ROWVEC, z.VARIANT_ALIGNED):
+        for variant in (z.VARIANT_ROWVEC, z.VARIANT_ALIGNED, z.VARIANT_HALFLINE):
             for unroll in (1, 2, 4, 8):
                 for line in (32, 64, 128, 256):
                     o = z.LaunchOpts(variant=variant, unroll=unroll, line_bytes=line)

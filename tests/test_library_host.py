@@ -102,6 +102,12 @@ def plan(row_elems, dtype, table_addr=0x7F0000000000, out_addr=0x7E0000000000, n
 def test_plan_picks_width_group_and_variant():
     p = plan(100, "f32")  # 400-byte rows: unaligned to 128 -> ALIGNED, 16-byte lanes
     assert (p["variant"], p["vec_bytes"], p["log2_group"], p["iters"]) == (z.VARIANT_ALIGNED, 16, 5, 1)
+    t = z.table_from_device(0x7F0000000000, 1000, 100, "f32")
+    t_host_like = z.plan_gather(t, 1000, 0x7E0000000000, z.LaunchOpts(variant=z.VARIANT_HALFLINE))
+    t.close()
+    assert (t_host_like["variant"], t_host_like["log2_group"]) == (z.VARIANT_HALFLINE, 5)
+    p = plan(99, "f16", variant=z.VARIANT_HALFLINE)  # 198-byte rows: no 4-byte granularity
+    assert p["variant"] == z.VARIANT_ALIGNED
     p = plan(602, "f32")  # 2,408-byte rows: 8-byte lanes, a wave per row, several passes
     assert (p["variant"], p["vec_bytes"], p["log2_group"]) == (z.VARIANT_ALIGNED, 8, 6)
     assert p["iters"] == -(-(2408 + 120) // 512)
@@ -123,8 +129,8 @@ def test_plan_picks_width_group_and_variant():
     assert p["blocks"] == 7
     p = plan(100, "f32", n_idx=3)
     assert p["blocks"] == 1
-    for bad in (dict(unroll=3), dict(line_bytes=48), dict(vec_bytes=2), dict(variant=4),
-                dict(nt_loads=3)):
+    for bad in (dict(unroll=3), dict(line_bytes=48), dict(vec_bytes=2), dict(variant=5),
+                dict(nt_loads=4)):
         with pytest.raises(z.ZcgError):
             plan(100, "f32", **bad)
 
