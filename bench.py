@@ -86,12 +86,72 @@ def build_workload(z, wl, k, n_batches, flags, max_table_gb):
                                    note=note, n_rows=n_rows)
 
 
+def run_sweep(args, z, wl, np, torch, link_peak):
+    """Config 5: 10 M rows x dim in {16,64,256,1024}, fp16 and fp32, 1 M uniform indices per call;
+    host-resident zero-copy vs the same table copied to HBM. One JSON line with all points."""
+    points = []
+    for cfg in wl.sweep_configs():
+        table = z.alloc_table(cfg.n_rows, cfg.dim, cfg.dtype)
+        wl.fill_table_ptr(table.host_ptr, cfg.n_rows, cfg.dim, cfg.dtype, cfg.seed)
+        idx = wl.index_lists(cfg)[0]
+        idx_dev = torch.from_numpy(idx).cuda()
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.float16
+        out = torch.empty((idx.size, cfg.dim), dtype=tdt, device="cuda")
+        stream = torch.cuda.current_stream()
+
+        def timed(t):
+            for _ in range(3):
+                z.gather(t, idx_dev, out, stream=stream)
+            torch.cuda.synchronize()
+            ms = []
+            for _ in range(max(5, min(args.steps, 20))):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                z.gather(t, idx_dev, out, stream=stream)
+                e1.record(stream)
+                e1.synchronize()
+                ms.append(e0.elapsed_time(e1))
+            return float(np.median(ms))
+
+        ms_host = timed(table)
+        hbm_t = torch.empty((cfg.n_rows, cfg.dim), dtype=tdt, device="cuda")
+        host = table.host_array()
+        step = max(1, (1 << 30) // cfg.row_bytes)
+        for lo in range(0, cfg.n_rows, step):
+            hbm_t[lo:lo + step].copy_(torch.from_numpy(host[lo:lo + step]))
+        t2 = z.table_from_device(hbm_t, cfg.n_rows, cfg.dim, cfg.dtype)
+        ms_hbm = timed(t2)
+        t2.close()
+        del hbm_t
+        useful = idx.size * cfg.row_bytes
+        staging = z.pinned_alloc(useful)
+        t0 = time.perf_counter()
+        for _ in range(3):
+            z.cpu_gather_memcpy_chunked(table, idx, staging, out, max(1024, (4 << 20) // cfg.row_bytes),
+                                        wl.default_threads(), stream)
+            torch.cuda.synchronize()
+        dma = useful * 3 / (time.perf_counter() - t0) / 1e9
+        z.pinned_free(staging)
+        lines = -(-cfg.row_bytes // 128)
+        points.append({"name": cfg.name, "row_bytes": cfg.row_bytes,
+                       "zero_copy_gbps": round(useful / ms_host / 1e6, 2),
+                       "fraction_of_link_peak": round(useful / ms_host / 1e6 / link_peak, 4),
+                       "rows_per_s": round(idx.size / ms_host * 1e3),
+                       "useful_over_line_bytes": round(cfg.row_bytes / (lines * 128), 3),
+                       "hbm_resident_gbps": round(useful / ms_hbm / 1e6, 1),
+                       "dma_chunked_gbps": round(dma, 2)})
+        table.close()
+        print(f"# {points[-1]}", file=sys.stderr, flush=True)
+    return points
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..4 (default 2, the metric's)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel (ablation)")
     ap.add_argument("--sorted", action="store_true", help="ascending index lists (secondary order)")
@@ -121,6 +181,15 @@ def main():
 
     link_peak = z.measure_h2d(1 << 30, 10)
     nominal, link_name = nominal_link_gbps()
+
+    if args.config == 5:
+        pts = run_sweep(args, z, wl, np, torch, link_peak)
+        print(json.dumps({"metric": METRIC, "unit": "GB/s", "n_gpus": 1, "data": "synthetic",
+                          "config": {"workload": "cfg5 width/dtype sweep: 10,000,000 rows x dim, "
+                                                 "1,000,000 uniform int64 indices per call"},
+                          "link": {"measured_h2d_gbps": round(link_peak, 2), "nominal_gbps": nominal},
+                          "sweep": pts}))
+        return
 
     cfg, table, lists, build_info = build_workload(z, wl, args.config, n_batches, z.ALLOC_DEFAULT,
                                                    args.max_table_gb)
