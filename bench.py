@@ -145,13 +145,63 @@ def run_sweep(args, z, wl, np, torch, link_peak):
     return points
 
 
+def run_align_sweep(args, z, wl, np, torch, link_peak):
+    """The paper's Section 4.2 experiment (its Figure 8) on synthetic data: rows of 1024...1044 bytes
+    (fp32 dim 256...261) in a 13.6 M-row table, sampled index lists; every kernel and the DMA method."""
+    n_rows, points = 13_600_000, []
+    g = wl.PowerLawGraph(n_rows, 32.0, 2.1, wl.MASTER_SEED + 6)
+    lists = [g.sample_minibatch(1024, (15, 10), b)[0] for b in range(8)]
+    g.close()
+    idx_dev = [torch.from_numpy(a).cuda() for a in lists]
+    stream = torch.cuda.current_stream()
+    for dim in range(256, 262):
+        rb = dim * 4
+        table = z.alloc_table(n_rows, dim, "f32")
+        wl.fill_table_ptr(table.host_ptr, n_rows, dim, "f32", wl.MASTER_SEED + 6)
+        out = torch.empty((max(a.size for a in lists), dim), dtype=torch.float32, device="cuda")
+        pt = {"row_bytes": rb}
+        for name, variant in (("naive", z.VARIANT_NAIVE), ("rowvec", z.VARIANT_ROWVEC),
+                              ("aligned", z.VARIANT_ALIGNED), ("halfline", z.VARIANT_HALFLINE),
+                              ("auto", z.VARIANT_AUTO)):
+            for b in range(2):
+                z.gather_variant(table, idx_dev[b], out, variant, stream=stream)
+            torch.cuda.synchronize()
+            tot_ms, rows = 0.0, 0
+            for i in range(max(8, min(args.steps, 40))):
+                b = i % len(lists)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                z.gather_variant(table, idx_dev[b], out, variant, stream=stream)
+                e1.record(stream)
+                e1.synchronize()
+                tot_ms += e0.elapsed_time(e1)
+                rows += lists[b].size
+            pt[name + "_gbps"] = round(rows * rb / tot_ms / 1e6, 2)
+            pt[name + "_frac"] = round(rows * rb / tot_ms / 1e6 / link_peak, 4)
+        staging = z.pinned_alloc(out.numel() * 4)
+        t0, rows = time.perf_counter(), 0
+        for b in range(len(lists)):
+            z.cpu_gather_memcpy_chunked(table, lists[b], staging, out, max(1024, (4 << 20) // rb),
+                                        wl.default_threads(), stream)
+            torch.cuda.synchronize()
+            rows += lists[b].size
+        pt["dma_chunked_gbps"] = round(rows * rb / (time.perf_counter() - t0) / 1e9, 2)
+        z.pinned_free(staging)
+        pt["plan_auto"] = z.VARIANT_NAMES[z.plan_gather(table, lists[0].size, out)["variant"]]
+        table.close()
+        points.append(pt)
+        print(f"# {pt}", file=sys.stderr, flush=True)
+    return points, int(np.mean([a.size for a in lists]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2,
-                    help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep")
+                    help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep; "
+                         "6 = alignment sweep, rows of 1024..1044 bytes")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel (ablation)")
     ap.add_argument("--sorted", action="store_true", help="ascending index lists (secondary order)")
@@ -187,6 +237,17 @@ def main():
         print(json.dumps({"metric": METRIC, "unit": "GB/s", "n_gpus": 1, "data": "synthetic",
                           "config": {"workload": "cfg5 width/dtype sweep: 10,000,000 rows x dim, "
                                                  "1,000,000 uniform int64 indices per call"},
+                          "link": {"measured_h2d_gbps": round(link_peak, 2), "nominal_gbps": nominal},
+                          "sweep": pts}))
+        return
+
+    if args.config == 6:
+        pts, avg_rows = run_align_sweep(args, z, wl, np, torch, link_peak)
+        print(json.dumps({"metric": METRIC, "unit": "GB/s", "n_gpus": 1, "data": "synthetic",
+                          "config": {"workload": "alignment sweep: fp32 table 13,600,000 x dim 256..261 "
+                                                 "(rows of 1024..1044 B), 1,024 seeds, fanout [15,10], "
+                                                 "dedup, power-law graph avg degree 32; 8 minibatches",
+                                     "rows_per_step_avg": avg_rows},
                           "link": {"measured_h2d_gbps": round(link_peak, 2), "nominal_gbps": nominal},
                           "sweep": pts}))
         return

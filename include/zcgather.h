@@ -53,8 +53,9 @@ extern "C" {
                                     GPU does not cache the table at all               */
 
 /* ---- gather kernels (zcg_gather_variant / zcg_gather_ex) --------------- */
-#define ZCG_VARIANT_AUTO 0    /* host table with partial row ends: HALFLINE; whole-line
-                                 rows: ROWVEC; HBM-resident table: ALIGNED / ROWVEC     */
+#define ZCG_VARIANT_AUTO 0    /* rows shorter than a line or made of whole lines: ROWVEC;
+                                 else ALIGNED, or HALFLINE for host-resident rows of at
+                                 least 1 KiB with 8-byte granularity                    */
 #define ZCG_VARIANT_NAIVE 1   /* one element per lane over the flat output, no alignment
                                  care: the paper's baseline kernel (Section 4.1.2 (c))  */
 #define ZCG_VARIANT_ROWVEC 2  /* a lane group per row, widest vector, loads start at the

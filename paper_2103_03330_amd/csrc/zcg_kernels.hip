@@ -421,14 +421,13 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   int unroll = o.unroll ? o.unroll : (host_resident ? 2 : 4);
   int vec_cap = o.vec_bytes ? o.vec_bytes : 16;
   if (!o.vec_bytes && host_resident) {
-    // Measured over the host link: a row spread over (nearly) all 64 lanes of one
-    // load instruction is slightly faster than the same row in 16-byte chunks on
-    // fewer lanes, so prefer the narrowest chunk that still fits one wave pass.
-    int pref = 4;
-    while (pref < 16 && (int64_t)pref * kWave < row_bytes) pref <<= 1;
+    // Measured over the host link: 8-byte lanes (a wave pass = 512 bytes = 4 lines) are as
+    // fast or slightly faster than 16-byte lanes for every row longer than a line; rows of
+    // at most one line do best with 16-byte lanes.
+    const int pref = row_bytes <= 128 ? 16 : 8;
     vec_cap = pref < elem ? elem : pref;
   }
-  int max_blocks = o.max_blocks ? o.max_blocks : (host_resident ? 2048 : 8192);
+  int max_blocks = o.max_blocks ? o.max_blocks : (host_resident && row_bytes > 128 ? 2048 : 8192);
   const int ntl = o.nt_loads == 1 ? 1 : (o.nt_loads == 3 ? 2 : 0);  // default: plain loads
   const int nts = o.nt_stores == 2 ? 0 : 1;                // default: non-temporal stores
   if (variant < 0 || variant >= ZCG_VARIANT_COUNT) return ZCG_EINVAL;
@@ -445,8 +444,9 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     while ((1 << min_lg) < o.group_lanes) ++min_lg;
   } else if (host_resident) {
     // Measured: over the host link one row per wave-wide load instruction is the
-    // fastest and the least sensitive to grid size and unrolling.
-    min_lg = 6;
+    // fastest and the least sensitive to grid size and unrolling; rows of at most
+    // one line do slightly better 16 lanes wide on a larger grid.
+    min_lg = row_bytes > 128 ? 6 : 4;
   }
 
   // Widest access that keeps every chunk of every row aligned at both ends.
@@ -461,10 +461,13 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   if (variant == ZCG_VARIANT_AUTO) {
     // Rows shorter than a line, or made of whole lines on a line-aligned base,
     // need no realignment (the paper's applicability rule, end of Section 3.2.1).
-    // HALFLINE is never chosen here: it lowers the bytes on the link but not the
-    // time (the link side serves requests at a fixed rate, half lines included).
     const bool whole_lines = (row_bytes % line == 0) && (table_addr % (uintptr_t)line == 0);
     variant = (row_bytes < line || whole_lines) ? ZCG_VARIANT_ROWVEC : ZCG_VARIANT_ALIGNED;
+    // Long unaligned rows over the host link: one half-line read per ~8+ lines is a net gain
+    // (measured +2...4 % on 1,032...2,408-byte rows with 8- or 16-byte lanes); on short rows
+    // it is a loss, with 4-byte lanes it is neutral.
+    if (variant == ZCG_VARIANT_ALIGNED && host_resident && w >= 8 && row_bytes >= 1024)
+      variant = ZCG_VARIANT_HALFLINE, line = 128;
   }
 
   plan->variant = variant;
