@@ -85,6 +85,11 @@ typedef struct zcg_launch_opts {
   int vec_bytes;   /* cap on bytes per lane access: 2, 4, 8 or 16                      */
   int group_lanes; /* lanes given to one row, a power of two up to 64; raised to what
                       the row needs. 64 = one row per wave-wide load instruction       */
+  int shifted_stores; /* ALIGNED with rows or bases less aligned than vec_bytes: 1 (and the
+                      default) keeps the loads vec_bytes wide at line-aligned positions and
+                      writes with narrower / unaligned stores; 2 narrows the loads instead.
+                      With wide loads, up to vec_bytes-1 bytes next to a row end, inside
+                      the same aligned vec_bytes block, are read and dropped.            */
 } zcg_launch_opts;
 
 /* How one gather call is laid out on the GPU; filled by zcg_plan_gather. */
@@ -98,6 +103,7 @@ typedef struct zcg_plan {
   int nt_loads;    /* 0 plain, 1 non-temporal, 2 system scope                          */
   int nt_stores;   /* 0 / 1                                                            */
   int blocks;      /* grid size, blocks of 256 lanes                                   */
+  int store_bytes; /* alignment the stores can rely on; < vec_bytes means shifted stores */
 } zcg_plan;
 
 /* ---- errors ------------------------------------------------------------ */

@@ -127,6 +127,119 @@ zcg_k_rows_wide(const uint8_t* __restrict__ table, const int64_t* __restrict__ i
 }
 
 // ---------------------------------------------------------------------------
+// Shifted-store kernels: ALIGNED for rows whose size or bases are only WS-byte
+// aligned (WS < W). Loads are still W-byte chunks at line-aligned positions
+// (always W-aligned, whatever the row start); a chunk that lies fully inside
+// the row is written with one W-byte store to a WS-aligned address, the (at
+// most two) chunks that straddle a row end are written element by element.
+// This is the paper's trade (Section 3.2.1): reads aligned, the misalignment
+// moved to the local writes -- at byte granularity instead of element rotation.
+// A straddling chunk is loaded whole: up to W-WS bytes next to the row inside
+// the same aligned W-byte block are read and dropped.
+// ---------------------------------------------------------------------------
+template <int W, int WS, bool NT>
+__device__ __forceinline__ void store_chunk_unaligned(uint8_t* p, typename vec_of<W>::type v) {
+  typedef typename vec_of<W>::type __attribute__((aligned(WS))) uvec;
+  auto* q = reinterpret_cast<uvec*>(p);
+  if constexpr (NT) __builtin_nontemporal_store(v, q);
+  else *q = v;
+}
+
+// off = position of the chunk's first byte relative to the row start (may be negative);
+// only bytes at positions [lo, hi) of the row are written.
+template <int W, int WS, bool NT>
+__device__ __forceinline__ void store_shifted(uint8_t* out_row, int64_t off, int64_t lo, int64_t hi,
+                                              typename vec_of<W>::type v) {
+  if constexpr (W == WS) {
+    store_chunk<W, NT>(out_row + off, v);  // chunks are never partial
+  } else {
+    if (off >= lo && off + W <= hi) {
+      store_chunk_unaligned<W, WS, NT>(out_row + off, v);
+    } else {
+      typedef typename vec_of<WS>::type elem_t;
+      elem_t e[W / WS];
+      __builtin_memcpy(e, &v, W);
+#pragma unroll
+      for (int k = 0; k < W / WS; ++k) {
+        const int64_t eo = off + (int64_t)k * WS;
+        if (eo >= lo && eo < hi) *reinterpret_cast<elem_t*>(out_row + eo) = e[k];
+      }
+    }
+  }
+}
+
+template <int W, int WS, int U, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+zcg_k_rows_narrow_shift(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
+                        int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g,
+                        unsigned line_mask) {
+  typedef typename vec_of<W>::type vec;
+  const unsigned lane = threadIdx.x & ((1u << log2_g) - 1u);
+  const int64_t n_groups = ((int64_t)gridDim.x * kBlock) >> log2_g;
+  const int64_t group = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> log2_g;
+  const int64_t lane_off = (int64_t)lane * W;
+  const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
+
+  for (int64_t base = group; base < n_idx; base += n_groups * U) {
+    int64_t row_id[U];
+    vec v[U];
+    int64_t off[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = base + (int64_t)u * n_groups;
+      row_id[u] = idx[r < n_idx ? r : n_idx - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = base + (int64_t)u * n_groups;
+      const uint8_t* src = table + row_id[u] * row_bytes;
+      off[u] = lane_off - (int64_t)((uintptr_t)src & line_mask);
+      ok[u] = (r < n_idx) && (off[u] > -(int64_t)W) && (off[u] < row_bytes);
+      v[u] = load_chunk<W, 0>(ok[u] ? src + off[u] : dummy);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t r = base + (int64_t)u * n_groups;
+      if (ok[u]) store_shifted<W, WS, NTS>(out + r * row_bytes, off[u], 0, row_bytes, v[u]);
+    }
+  }
+}
+
+template <int W, int WS, int U, bool NTS>
+__global__ void __launch_bounds__(kBlock)
+zcg_k_rows_wide_shift(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
+                      int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes,
+                      unsigned line_mask) {
+  typedef typename vec_of<W>::type vec;
+  const unsigned lane = threadIdx.x & (kWave - 1);
+  const int64_t n_waves = ((int64_t)gridDim.x * kBlock) / kWave;
+  const int64_t wave = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kWave;
+  constexpr int64_t kStep = (int64_t)kWave * W;
+  const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
+
+  for (int64_t r = wave; r < n_idx; r += n_waves) {
+    const uint8_t* src = table + idx[r] * row_bytes;
+    const int64_t mis = (int64_t)((uintptr_t)src & line_mask);
+    uint8_t* out_row = out + r * row_bytes;
+    // off walks the chunks of the line-aligned span, relative to the row start
+    for (int64_t off0 = (int64_t)lane * W - mis; off0 < row_bytes; off0 += kStep * U) {
+      vec v[U];
+      bool ok[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t off = off0 + (int64_t)u * kStep;
+        ok[u] = (off > -(int64_t)W) && (off < row_bytes);
+        v[u] = load_chunk<W, 0>(ok[u] ? src + off : dummy);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (ok[u]) store_shifted<W, WS, NTS>(out_row, off0 + (int64_t)u * kStep, 0, row_bytes, v[u]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // HALFLINE kernels.
 //
 // Measured on gfx950: a vector load of mapped host memory always costs whole
@@ -196,7 +309,7 @@ __device__ __forceinline__ void move_pieces(const RowSplit& sp, uint64_t S, uint
   if (mine) *reinterpret_cast<uint32_t*>(out_row + (a - S)) = is_head_lane ? h : t;
 }
 
-template <int W, int U, bool NTS>
+template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
                        int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g) {
@@ -215,7 +328,7 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
     int64_t row_id[U];
     uint64_t src[U];
     vec v[U];
-    int64_t dst[U];
+    bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = wbase + my_group + (int64_t)u * n_groups;
@@ -228,10 +341,9 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
       src[u] = S;
       const RowSplit sp = split_row(S, (uint64_t)row_bytes);
       const uint64_t a = (S & ~(uint64_t)127u) + (uint64_t)lane_off;  // line-aligned lane mapping
-      const bool ok = (r < n_idx) && (a >= sp.vs) && (a < sp.ve);
+      ok[u] = (r < n_idx) && (a + W > sp.vs) && (a < sp.ve);
       // pointer formed from `table` so that the load stays a global (not flat) access
-      v[u] = load_chunk<W, 0>(ok ? table + (a - (uint64_t)(uintptr_t)table) : dummy);
-      dst[u] = ok ? r * row_bytes + (int64_t)(a - S) : -1;
+      v[u] = load_chunk<W, 0>(ok[u] ? table + (a - (uint64_t)(uintptr_t)table) : dummy);
     }
     // row ends through the scalar cache, one row of the wave at a time
 #pragma unroll
@@ -247,12 +359,19 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
       }
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (dst[u] >= 0) store_chunk<W, NTS>(out + dst[u], v[u]);
+    for (int u = 0; u < U; ++u) {
+      if (ok[u]) {
+        const int64_t r = wbase + my_group + (int64_t)u * n_groups;
+        const RowSplit sp = split_row(src[u], (uint64_t)row_bytes);
+        const int64_t off = (int64_t)((src[u] & ~(uint64_t)127u) + (uint64_t)lane_off - src[u]);
+        store_shifted<W, WS, NTS>(out + r * row_bytes, off, (int64_t)(sp.vs - src[u]),
+                                  (int64_t)(sp.ve - src[u]), v[u]);
+      }
+    }
   }
 }
 
-template <int W, int U, bool NTS>
+template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
                      int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes) {
@@ -275,12 +394,14 @@ zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restric
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint64_t au = a + (uint64_t)u * kStep;
-        ok[u] = (au >= sp.vs) && (au < sp.ve);
+        ok[u] = (au + W > sp.vs) && (au < sp.ve);
         v[u] = load_chunk<W, 0>(ok[u] ? table + (au - (uint64_t)(uintptr_t)table) : dummy);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (ok[u]) store_chunk<W, NTS>(out_row + (a + (uint64_t)u * kStep - S), v[u]);
+        if (ok[u])
+          store_shifted<W, WS, NTS>(out_row, (int64_t)(a + (uint64_t)u * kStep - S),
+                                    (int64_t)(sp.vs - S), (int64_t)(sp.ve - S), v[u]);
     }
   }
 }
@@ -334,16 +455,16 @@ hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* i
     if (p.variant == ZCG_VARIANT_HALFLINE) {
       if (p.iters == 1) {
         if (p.nt_stores)
-          zcg_k_rows_narrow_half<W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+          zcg_k_rows_narrow_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
                                                                      row_bytes, p.log2_group);
         else
-          zcg_k_rows_narrow_half<W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+          zcg_k_rows_narrow_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
                                                                       row_bytes, p.log2_group);
       } else {
         if (p.nt_stores)
-          zcg_k_rows_wide_half<W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes);
+          zcg_k_rows_wide_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes);
         else
-          zcg_k_rows_wide_half<W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes);
+          zcg_k_rows_wide_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes);
       }
       return hipGetLastError();
     }
@@ -377,6 +498,61 @@ hipError_t launch_rows_u(const zcg_plan& p, const uint8_t* table, const int64_t*
     case 2: return launch_rows<W, 2>(p, table, idx, n_idx, out, row_bytes, s);
     case 4: return launch_rows<W, 4>(p, table, idx, n_idx, out, row_bytes, s);
     case 8: return launch_rows<W, 8>(p, table, idx, n_idx, out, row_bytes, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <int W, int WS, int U>
+hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* idx, int64_t n_idx,
+                        uint8_t* out, int64_t row_bytes, hipStream_t s) {
+  const unsigned mask = (unsigned)(p.line_bytes - 1);
+  const dim3 grid((unsigned)p.blocks), block(kBlock);
+  if constexpr (WS >= 4) {
+    if (p.variant == ZCG_VARIANT_HALFLINE) {
+      if (p.iters == 1) {
+        if (p.nt_stores)
+          zcg_k_rows_narrow_half<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                         row_bytes, p.log2_group);
+        else
+          zcg_k_rows_narrow_half<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                          row_bytes, p.log2_group);
+      } else {
+        if (p.nt_stores)
+          zcg_k_rows_wide_half<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                       row_bytes);
+        else
+          zcg_k_rows_wide_half<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                        row_bytes);
+      }
+      return hipGetLastError();
+    }
+  }
+  if (p.iters == 1) {
+    if (p.nt_stores)
+      zcg_k_rows_narrow_shift<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                      row_bytes, p.log2_group, mask);
+    else
+      zcg_k_rows_narrow_shift<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                       row_bytes, p.log2_group, mask);
+  } else {
+    if (p.nt_stores)
+      zcg_k_rows_wide_shift<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes,
+                                                                    mask);
+    else
+      zcg_k_rows_wide_shift<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+                                                                     row_bytes, mask);
+  }
+  return hipGetLastError();
+}
+
+template <int W, int WS>
+hipError_t launch_shift_u(const zcg_plan& p, const uint8_t* table, const int64_t* idx,
+                          int64_t n_idx, uint8_t* out, int64_t row_bytes, hipStream_t s) {
+  switch (p.unroll) {
+    case 1: return launch_shift<W, WS, 1>(p, table, idx, n_idx, out, row_bytes, s);
+    case 2: return launch_shift<W, WS, 2>(p, table, idx, n_idx, out, row_bytes, s);
+    case 4: return launch_shift<W, WS, 4>(p, table, idx, n_idx, out, row_bytes, s);
+    case 8: return launch_shift<W, WS, 8>(p, table, idx, n_idx, out, row_bytes, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -436,7 +612,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   if (vec_cap != 2 && vec_cap != 4 && vec_cap != 8 && vec_cap != 16) return ZCG_EINVAL;
   if (max_blocks < 1 || o.nt_loads < 0 || o.nt_loads > 3 || o.nt_stores < 0 || o.nt_stores > 2)
     return ZCG_EINVAL;
-  if (vec_cap < elem) return ZCG_EINVAL;
+  if (vec_cap < elem || o.shifted_stores < 0 || o.shifted_stores > 2) return ZCG_EINVAL;
   int min_lg = 0;
   if (o.group_lanes) {
     if (o.group_lanes < 1 || o.group_lanes > kWave || (o.group_lanes & (o.group_lanes - 1)))
@@ -466,7 +642,8 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     // Long unaligned rows over the host link: one half-line read per ~8+ lines is a net gain
     // (measured +2...4 % on 1,032...2,408-byte rows with 8- or 16-byte lanes); on short rows
     // it is a loss, with 4-byte lanes it is neutral.
-    if (variant == ZCG_VARIANT_ALIGNED && host_resident && w >= 8 && row_bytes >= 1024)
+    if (variant == ZCG_VARIANT_ALIGNED && host_resident && row_bytes >= 1024 &&
+        (w >= 8 || (w >= 4 && vec_cap >= 8 && o.shifted_stores != 2)))
       variant = ZCG_VARIANT_HALFLINE, line = 128;
   }
 
@@ -479,16 +656,23 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   int64_t want_blocks;
   if (variant == ZCG_VARIANT_NAIVE) {
     plan->vec_bytes = elem;
+    plan->store_bytes = elem;
     plan->log2_group = 0;
     plan->iters = 1;
     plan->unroll = 1;
     const int64_t total = n_idx * (row_bytes / elem);
     want_blocks = (total + kBlock - 1) / kBlock;
   } else {
-    plan->vec_bytes = w;
+    // ALIGNED loads sit at line-aligned positions, so they can stay vec_cap wide when the
+    // rows or bases are less aligned than that; only the stores drop to w (shifted stores).
     const bool line_mapped = variant == ZCG_VARIANT_ALIGNED || variant == ZCG_VARIANT_HALFLINE;
+    int wl = w;
+    if (line_mapped && w < vec_cap && vec_cap >= 8 && o.shifted_stores != 2)
+      wl = vec_cap;
+    plan->vec_bytes = wl;
+    plan->store_bytes = w;
     const int64_t worst_span = row_bytes + (line_mapped ? line - w : 0);
-    const int64_t chunks = (worst_span + w - 1) / w;
+    const int64_t chunks = (worst_span + wl - 1) / wl;
     int lg = 0;
     while (lg < 6 && ((int64_t)1 << lg) < chunks) ++lg;
     if (lg < min_lg) lg = min_lg;
@@ -517,6 +701,16 @@ hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t
   }
   const uint8_t* t = static_cast<const uint8_t*>(table);
   uint8_t* o = static_cast<uint8_t*>(out);
+  if (p.store_bytes < p.vec_bytes) {
+    switch (p.vec_bytes * 100 + p.store_bytes) {
+      case 1608: return launch_shift_u<16, 8>(p, t, idx, n_idx, o, row_bytes, stream);
+      case 1604: return launch_shift_u<16, 4>(p, t, idx, n_idx, o, row_bytes, stream);
+      case 1602: return launch_shift_u<16, 2>(p, t, idx, n_idx, o, row_bytes, stream);
+      case 804: return launch_shift_u<8, 4>(p, t, idx, n_idx, o, row_bytes, stream);
+      case 802: return launch_shift_u<8, 2>(p, t, idx, n_idx, o, row_bytes, stream);
+      default: return hipErrorInvalidValue;
+    }
+  }
   switch (p.vec_bytes) {
     case 16: return launch_rows_u<16>(p, t, idx, n_idx, o, row_bytes, stream);
     case 8: return launch_rows_u<8>(p, t, idx, n_idx, o, row_bytes, stream);

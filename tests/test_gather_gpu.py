@@ -91,6 +91,9 @@ def test_launch_knobs_do_not_change_the_result(dim, dtype):
                     continue
                 o = z.LaunchOpts(variant=variant, vec_bytes=vec, nt_loads=1, nt_stores=2)
                 assert_same_bits(run_gather(table, idx, dtype, o), want, f"vec{vec}")
+            for vec in (8, 16):  # narrow loads instead of shifted stores
+                o = z.LaunchOpts(variant=variant, vec_bytes=vec, shifted_stores=2, group_lanes=16)
+                assert_same_bits(run_gather(table, idx, dtype, o), want, f"noshift vec{vec}")
             # one block only: the grid-stride loop does all the work
             o = z.LaunchOpts(variant=variant, max_blocks=1)
             assert_same_bits(run_gather(table, idx, dtype, o), want, "max_blocks=1")

@@ -109,18 +109,22 @@ def test_plan_picks_width_group_and_variant():
     p = plan(99, "f16", variant=z.VARIANT_HALFLINE)  # 198-byte rows: no 4-byte granularity
     assert p["variant"] == z.VARIANT_ALIGNED
     p = plan(602, "f32")  # 2,408-byte rows: 8-byte lanes, a wave per row, several passes
-    assert (p["variant"], p["vec_bytes"], p["log2_group"]) == (z.VARIANT_ALIGNED, 8, 6)
-    assert p["iters"] == -(-(2408 + 120) // 512)
+    assert (p["variant"], p["vec_bytes"], p["store_bytes"], p["log2_group"]) == (z.VARIANT_ALIGNED, 16, 8, 6)
+    assert p["iters"] == -(-(2408 + 120) // 1024)
+    p = plan(602, "f32", shifted_stores=2)  # loads narrowed to the rows' own 8-byte alignment
+    assert (p["vec_bytes"], p["store_bytes"], p["iters"]) == (8, 8, -(-(2408 + 120) // 512))
     p = plan(128, "f32")  # whole lines on an aligned base: no realignment needed
     assert (p["variant"], p["vec_bytes"], p["log2_group"], p["iters"]) == (z.VARIANT_ROWVEC, 16, 5, 1)
     p = plan(16, "f16")  # 32-byte rows, shorter than a line
     assert (p["variant"], p["vec_bytes"], p["log2_group"]) == (z.VARIANT_ROWVEC, 16, 1)
     p = plan(128, "f32", table_addr=0x7F0000000040)  # same rows on a base 64 bytes off the line
     assert p["variant"] == z.VARIANT_ALIGNED
-    p = plan(100, "f32", table_addr=0x7F0000000004)  # base only element-aligned
-    assert p["vec_bytes"] == 4
+    p = plan(100, "f32", table_addr=0x7F0000000004)  # base only element-aligned: shifted stores
+    assert (p["vec_bytes"], p["store_bytes"]) == (16, 4)
     p = plan(100, "f32", out_addr=0x7E0000000008)
-    assert p["vec_bytes"] == 8
+    assert (p["vec_bytes"], p["store_bytes"]) == (16, 8)
+    p = plan(100, "f32", out_addr=0x7E0000000008, variant=z.VARIANT_ROWVEC)
+    assert (p["vec_bytes"], p["store_bytes"]) == (8, 8)
     p = plan(3, "f16")
     assert p["vec_bytes"] == 2
     p = plan(100, "f32", variant=z.VARIANT_NAIVE)
@@ -130,7 +134,7 @@ def test_plan_picks_width_group_and_variant():
     p = plan(100, "f32", n_idx=3)
     assert p["blocks"] == 1
     for bad in (dict(unroll=3), dict(line_bytes=48), dict(vec_bytes=2), dict(variant=5),
-                dict(nt_loads=4)):
+                dict(nt_loads=4), dict(shifted_stores=3)):
         with pytest.raises(z.ZcgError):
             plan(100, "f32", **bad)
 
@@ -146,8 +150,10 @@ def covered_bytes(row_bytes, src_addr, p):
     for it in range(p["iters"]):
         for lane in range(g):
             off = (it * g + lane) * w - mis
-            if 0 <= off < row_bytes:
-                pairs.extend((src_addr + off + b, off + b) for b in range(w))
+            if -w < off < row_bytes:  # the chunk meets the row; bytes outside it are dropped
+                assert (src_addr + off) % w == 0 or p["store_bytes"] == w
+                pairs.extend((src_addr + off + b, off + b) for b in range(w)
+                             if 0 <= off + b < row_bytes)
     return sorted(pairs)
 
 
