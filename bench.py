@@ -194,6 +194,109 @@ def run_align_sweep(args, z, wl, np, torch, link_peak):
     return points, int(np.mean([a.size for a in lists]))
 
 
+def run_provisioning(args, z, wl, np, torch, link_peak):
+    """Section 3.2.2 / 4.3 of the paper on one MI355X: how much of the GPU the gather needs, and what
+    capping its share buys when compute kernels run beside it. The share is set by binding the
+    gather's stream to a subset of the compute units (the paper used a process-level service)."""
+    cfg, table, lists, _ = build_workload(z, wl, 2, 16, z.ALLOC_DEFAULT, args.max_table_gb)
+    rb = cfg.row_bytes
+    idx_dev = [torch.from_numpy(a).cuda() for a in lists]
+    outs = [torch.empty((max(a.size for a in lists), cfg.dim), dtype=torch.float32, device="cuda")
+            for _ in range(2)]
+    n_cus = z.device_cu_count(0)
+    reps = max(16, min(args.steps, 64))
+
+    def spread(n):
+        # bit i of the mask is compute unit i/8 of accelerator die i%8: the first n bits, n a
+        # multiple of 8, take n/8 compute units on each of the 8 dies (the runtime refuses a
+        # mask that leaves a die without any)
+        return list(range(n))
+
+    def gather_rate(stream_obj, opts=None):
+        ts = torch.cuda.ExternalStream(stream_obj.cuda_stream) if hasattr(stream_obj, "cu_ids") else stream_obj
+        for i in range(3):
+            z.gather_ex(table, idx_dev[i % 16], outs[i & 1], opts, n_idx=lists[i % 16].size, stream=ts)
+        ts.synchronize()
+        tot, rows = 0.0, 0
+        for i in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(ts)
+            z.gather_ex(table, idx_dev[i % 16], outs[i & 1], opts, n_idx=lists[i % 16].size, stream=ts)
+            e1.record(ts)
+            e1.synchronize()
+            tot += e0.elapsed_time(e1)
+            rows += lists[i % 16].size
+        return rows * rb / tot / 1e6
+
+    share_curve = []
+    for n in (8, 16, 24, 32, 40, 64, 128, 256):
+        n = min(n, n_cus)
+        ms = z.stream_create_cu_mask(spread(n))
+        g = gather_rate(ms)
+        ms.close()
+        share_curve.append({"cus": n, "share_percent": round(100.0 * n / n_cus, 1), "gbps": round(g, 2),
+                            "fraction_of_link_peak": round(g / link_peak, 4)})
+        print(f"# {share_curve[-1]}", file=sys.stderr, flush=True)
+    grid_curve = []
+    cur = torch.cuda.current_stream()
+    for blocks in (4, 8, 16, 32, 64, 128, 256, 2048):
+        g = gather_rate(cur, z.LaunchOpts(max_blocks=blocks))
+        grid_curve.append({"blocks": blocks, "waves": blocks * 4, "gbps": round(g, 2),
+                           "fraction_of_link_peak": round(g / link_peak, 4)})
+        print(f"# {grid_curve[-1]}", file=sys.stderr, flush=True)
+
+    # overlap with a compute kernel that fills the GPU: per minibatch one gather + one compute
+    sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+    comp_blocks = n_cus * 64  # many short blocks: no tail when some compute units are masked off
+    iters = 4000
+    z.synthetic_compute(cur, comp_blocks, iters, sink)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        z.synthetic_compute(cur, comp_blocks, iters, sink)
+    torch.cuda.synchronize()
+    per = (time.perf_counter() - t0) / 5
+    iters = max(1000, int(iters * 2.0e-3 / per))  # about 2 ms alone: twice one gather
+
+    def minibatch_ms(gs, cs, same_stream=False):
+        for s_ in {gs, cs}:
+            s_.synchronize()
+        t = time.perf_counter()
+        for i in range(reps):
+            z.gather_ex(table, idx_dev[i % 16], outs[i & 1], None, n_idx=lists[i % 16].size, stream=gs)
+            z.synthetic_compute(cs if not same_stream else gs, comp_blocks, iters, sink)
+        gs.synchronize()
+        cs.synchronize()
+        return (time.perf_counter() - t) / reps * 1e3
+
+    z.synthetic_compute(cur, comp_blocks, iters, sink)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        z.synthetic_compute(cur, comp_blocks, iters, sink)
+    torch.cuda.synchronize()
+    compute_alone = (time.perf_counter() - t0) / reps * 1e3
+    gather_alone = float(np.mean([a.size for a in lists])) * rb / gather_rate(cur) / 1e6
+    overlap = [{"mode": "one stream (serial)", "ms_per_minibatch": round(minibatch_ms(cur, cur, True), 3)}]
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    overlap.append({"mode": "two streams, no masks", "ms_per_minibatch": round(minibatch_ms(s1, s2), 3)})
+    for n in (8, 16, 24, 40, 64, 128):
+        n = min(n, n_cus - 8)
+        gcu = spread(n)
+        ccu = [c for c in range(n_cus) if c not in set(gcu)]
+        mg, mc = z.stream_create_cu_mask(gcu), z.stream_create_cu_mask(ccu)
+        tg, tc = torch.cuda.ExternalStream(mg.cuda_stream), torch.cuda.ExternalStream(mc.cuda_stream)
+        overlap.append({"mode": f"masks {n}:{n_cus - n} CUs ({100.0 * n / n_cus:.1f}% gather)",
+                        "ms_per_minibatch": round(minibatch_ms(tg, tc), 3)})
+        mg.close()
+        mc.close()
+        print(f"# {overlap[-1]}", file=sys.stderr, flush=True)
+    table.close()
+    return {"gather_vs_cu_share": share_curve, "gather_vs_grid_size": grid_curve,
+            "overlap": {"gather_alone_ms": round(gather_alone, 3), "compute_alone_ms": round(compute_alone, 3),
+                        "compute_blocks": comp_blocks, "compute_iters": iters, "cases": overlap}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -201,7 +304,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep; "
-                         "6 = alignment sweep, rows of 1024..1044 bytes")
+                         "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel (ablation)")
     ap.add_argument("--sorted", action="store_true", help="ascending index lists (secondary order)")
@@ -241,6 +344,15 @@ def main():
                           "sweep": pts}))
         return
 
+    if args.config == 7:
+        res = run_provisioning(args, z, wl, np, torch, link_peak)
+        print(json.dumps({"metric": METRIC, "unit": "GB/s", "n_gpus": 1, "data": "synthetic",
+                          "config": {"workload": "resource provisioning on config 2 (400 B rows): gather "
+                                                 "bandwidth vs compute-unit share and grid size; overlap "
+                                                 "with a synthetic compute kernel"},
+                          "link": {"measured_h2d_gbps": round(link_peak, 2), "nominal_gbps": nominal},
+                          "provisioning": res}))
+        return
     if args.config == 6:
         pts, avg_rows = run_align_sweep(args, z, wl, np, torch, link_peak)
         print(json.dumps({"metric": METRIC, "unit": "GB/s", "n_gpus": 1, "data": "synthetic",

@@ -222,6 +222,30 @@ int zcg_cpu_gather_memcpy_chunked(const zcg_table* t, const int64_t* idx_host, i
  */
 int zcg_measure_h2d(int64_t bytes, int reps, int device, double* gb_per_s);
 
+/*
+ * Resource provisioning (Section 3.2.2: the gather needs only a small share of
+ * the GPU to saturate the link, the rest stays free for compute kernels). The
+ * paper caps the gather's share with a process-level service; here a stream is
+ * bound to a set of compute units instead, inside one process.
+ *   mask_words : host, n_words x 32 bits, bit i = compute unit i may run work of
+ *                this stream; at least one bit must be set among the device's CUs
+ * On this chip bit i is compute unit i/8 of accelerator die i%8, and the runtime
+ * refuses (ZCG_EHIP) a mask that leaves one of the 8 dies without a compute
+ * unit: the first n bits with n a multiple of 8 give n/8 units on every die.
+ * Default priority. Destroy with zcg_stream_destroy (waits for the stream).
+ */
+int zcg_stream_create_cu_mask(int device, const uint32_t* mask_words, int n_words, void** stream);
+int zcg_stream_destroy(void* stream);
+int zcg_device_cu_count(int device, int* n_cus);
+
+/*
+ * A stand-in for the training kernels the gather overlaps with (Section 3.2.2,
+ * Section 4.3): `blocks` blocks of 256 lanes, each lane runs `iters` dependent
+ * fused multiply-adds and adds its result into sink_dev[lane id mod 256]
+ * (device, 256 floats, CALLER-OWNED). Pure ALU work, asynchronous on `stream`.
+ */
+int zcg_synthetic_compute(void* stream, int blocks, int64_t iters, float* sink_dev);
+
 /* Pinned host scratch for callers without another allocator (staging buffers). */
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr);
 int zcg_pinned_free(void* host_ptr);

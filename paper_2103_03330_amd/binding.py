@@ -35,7 +35,8 @@ EXPORTS = [
     "zcg_table_n_rows", "zcg_unregister_table", "zcg_gather", "zcg_gather_variant",
     "zcg_gather_ex", "zcg_plan_gather", "zcg_validate_indices", "zcg_cpu_gather_memcpy",
     "zcg_cpu_gather_memcpy_chunked", "zcg_measure_h2d", "zcg_pinned_alloc", "zcg_pinned_free",
-    "zcg_version",
+    "zcg_version", "zcg_stream_create_cu_mask", "zcg_stream_destroy", "zcg_device_cu_count",
+    "zcg_synthetic_compute",
 ]
 
 
@@ -103,6 +104,10 @@ def load_library() -> ctypes.CDLL:
         "zcg_measure_h2d": (i32, [i64, i32, i32, ctypes.POINTER(ctypes.c_double)]),
         "zcg_pinned_alloc": (i32, [i64, pvp]),
         "zcg_pinned_free": (i32, [vp]),
+        "zcg_stream_create_cu_mask": (i32, [i32, ctypes.POINTER(ctypes.c_uint32), i32, pvp]),
+        "zcg_stream_destroy": (i32, [vp]),
+        "zcg_device_cu_count": (i32, [i32, ctypes.POINTER(i32)]),
+        "zcg_synthetic_compute": (i32, [vp, i32, i64, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -322,3 +327,43 @@ def pinned_alloc(n_bytes: int) -> int:
 
 def pinned_free(ptr: int) -> None:
     _check(load_library().zcg_pinned_free(ptr), "zcg_pinned_free")
+
+
+def device_cu_count(device: int = 0) -> int:
+    n = ctypes.c_int(0)
+    _check(load_library().zcg_device_cu_count(device, ctypes.byref(n)), "zcg_device_cu_count")
+    return int(n.value)
+
+
+class MaskedStream:
+    """A HIP stream bound to a set of compute units (zcg_stream_create_cu_mask)."""
+
+    def __init__(self, cu_ids, device: int = 0, n_words: int = 8):
+        words = (ctypes.c_uint32 * n_words)()
+        for c in cu_ids:
+            if not 0 <= c < n_words * 32:
+                raise ValueError("compute unit id out of range")
+            words[c // 32] |= 1 << (c % 32)
+        out = ctypes.c_void_p()
+        _check(load_library().zcg_stream_create_cu_mask(device, words, n_words, ctypes.byref(out)),
+               "zcg_stream_create_cu_mask")
+        self.cuda_stream = int(out.value)
+        self.cu_ids = list(cu_ids)
+
+    def close(self) -> None:
+        if self.cuda_stream:
+            h, self.cuda_stream = self.cuda_stream, 0
+            _check(load_library().zcg_stream_destroy(h), "zcg_stream_destroy")
+
+
+def stream_create_cu_mask(cu_ids, device: int = 0) -> MaskedStream:
+    return MaskedStream(cu_ids, device)
+
+
+def stream_destroy(stream: MaskedStream) -> None:
+    stream.close()
+
+
+def synthetic_compute(stream, blocks: int, iters: int, sink_dev) -> None:
+    _check(load_library().zcg_synthetic_compute(_stream(stream), blocks, iters, _ptr(sink_dev)),
+           "zcg_synthetic_compute")

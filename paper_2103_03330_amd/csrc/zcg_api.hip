@@ -289,6 +289,47 @@ int zcg_measure_h2d(int64_t bytes, int reps, int device, double* gb_per_s) {
   return ZCG_OK;
 }
 
+int zcg_device_cu_count(int device, int* n_cus) {
+  if (device < 0 || !n_cus) return ZCG_EINVAL;
+  int v = 0;
+  hipError_t e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device);
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  *n_cus = v;
+  return ZCG_OK;
+}
+
+int zcg_stream_create_cu_mask(int device, const uint32_t* mask_words, int n_words, void** stream) {
+  if (device < 0 || !mask_words || n_words < 1 || n_words > 64 || !stream) return ZCG_EINVAL;
+  *stream = nullptr;
+  int n_cus = 0;
+  int rc = zcg_device_cu_count(device, &n_cus);
+  if (rc) return rc;
+  int enabled = 0;
+  for (int i = 0; i < n_cus && i < n_words * 32; ++i) enabled += (mask_words[i / 32] >> (i % 32)) & 1u;
+  if (enabled == 0) return ZCG_EINVAL;  // a stream that can run nowhere would hang its first kernel
+  DeviceScope scope(device);
+  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
+  hipStream_t s = nullptr;
+  hipError_t e = hipExtStreamCreateWithCUMask(&s, (uint32_t)n_words, mask_words);
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  *stream = s;
+  return ZCG_OK;
+}
+
+int zcg_stream_destroy(void* stream) {
+  if (!stream) return ZCG_EINVAL;
+  hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+  if (e == hipSuccess) e = hipStreamDestroy(static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
+}
+
+int zcg_synthetic_compute(void* stream, int blocks, int64_t iters, float* sink_dev) {
+  if (blocks < 1 || blocks > (1 << 20) || iters < 0 || iters > ((int64_t)1 << 32) || !sink_dev)
+    return ZCG_EINVAL;
+  hipError_t e = zcg_launch_synthetic_compute(static_cast<hipStream_t>(stream), blocks, iters, sink_dev);
+  return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
+}
+
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr) {
   if (bytes <= 0 || !host_ptr) return ZCG_EINVAL;
   *host_ptr = nullptr;

@@ -440,6 +440,14 @@ zcg_k_validate(const int64_t* __restrict__ idx, int64_t n_idx, int64_t n_rows,
   if (bad) atomicAdd(n_bad, bad);
 }
 
+// ALU-bound stand-in for a training kernel: a chain of dependent FMAs per lane.
+__global__ void __launch_bounds__(kBlock)
+zcg_k_synthetic_compute(int64_t iters, float* __restrict__ sink) {
+  float a = 1.0f + (float)threadIdx.x * 1e-6f, b = 0.999999f, c = 1e-7f;
+  for (int64_t i = 0; i < iters; ++i) a = __builtin_fmaf(a, b, c);
+  atomicAdd(&sink[threadIdx.x], a);
+}
+
 int floor_pow2_divisor(uint64_t x, int cap) {  // largest power of two <= cap dividing x
   int w = cap;
   while (w > 1 && (x % (uint64_t)w) != 0) w >>= 1;
@@ -718,6 +726,11 @@ hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t
     case 2: return launch_rows_u<2>(p, t, idx, n_idx, o, row_bytes, stream);
     default: return hipErrorInvalidValue;
   }
+}
+
+hipError_t zcg_launch_synthetic_compute(hipStream_t stream, int blocks, int64_t iters, float* sink) {
+  zcg_k_synthetic_compute<<<dim3((unsigned)blocks), dim3(kBlock), 0, stream>>>(iters, sink);
+  return hipGetLastError();
 }
 
 hipError_t zcg_launch_validate(const int64_t* idx, int64_t n_idx, int64_t n_rows,

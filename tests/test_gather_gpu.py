@@ -234,3 +234,35 @@ def test_gather_on_a_side_stream():
         assert_same_bits(out, want, "side stream")
     finally:
         table.close()
+
+
+def test_gather_on_a_cu_masked_stream():
+    """Resource provisioning: a stream bound to a few compute units still gathers correctly."""
+    n_rows, dim = 5000, 100
+    table = host_table(n_rows, dim, "f32", seed=12)
+    try:
+        idx = wl.uniform_indices(30000, n_rows, seed=5)
+        want = oracle_gather(table.host_array(), idx)
+        idx_dev = torch.from_numpy(idx).cuda()
+        n_cus = z.device_cu_count(0)
+        assert n_cus >= 8
+        for cus in (list(range(8)), list(range(40)), list(range(8, n_cus)), list(range(n_cus))):
+            ms = z.stream_create_cu_mask(cus)
+            out = torch.zeros((idx.size, dim), dtype=torch.float32, device="cuda")
+            torch.cuda.synchronize()
+            z.gather(table, idx_dev, out, stream=ms)
+            sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+            z.synthetic_compute(ms, 64, 1000, sink)
+            ms.close()  # waits for the stream
+            assert_same_bits(out, want, f"masked stream, {len(cus)} CUs")
+            assert float(sink.sum()) > 0
+        with pytest.raises(z.ZcgError) as e:  # a mask with no compute unit of the device
+            z.stream_create_cu_mask([])
+        assert e.value.status == -1
+        with pytest.raises(z.ZcgError) as e:  # a die left without compute units: the runtime refuses
+            z.stream_create_cu_mask([0])
+        assert e.value.status == -4
+        z.gather(table, idx_dev, out)  # the refusal leaves no error behind
+        torch.cuda.synchronize()
+    finally:
+        table.close()
