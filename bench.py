@@ -297,6 +297,82 @@ def run_provisioning(args, z, wl, np, torch, link_peak):
                         "compute_blocks": comp_blocks, "compute_iters": iters, "cases": overlap}}
 
 
+def run_pipeline(args, z, wl, np, torch, link_peak):
+    """Section 3.3 of the paper on one MI355X: sampler -> producer (list copy + gather) -> consumer
+    (a synthetic compute kernel standing in for training) with two alternating GPU buffers and one
+    event hand-off per minibatch, against the same work done step by step on one stream."""
+    cfg, table, lists, _ = build_workload(z, wl, 2, 16, z.ALLOC_DEFAULT, args.max_table_gb)
+    rb, n_cus = cfg.row_bytes, z.device_cu_count(0)
+    max_rows = max(a.size for a in lists)
+    reps = max(32, min(args.steps, 128))
+    sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+    comp_blocks, iters = n_cus * 64, 6000  # about 2 ms on the whole GPU
+    bufs = [torch.empty((max_rows, cfg.dim), dtype=torch.float32, device="cuda") for _ in range(2)]
+    cur = torch.cuda.current_stream()
+
+    # step by step on one stream: copy list, gather, compute, wait
+    idx_dev = torch.empty(max_rows, dtype=torch.int64, device="cuda")
+    pinned = [torch.from_numpy(a).pin_memory() for a in lists]
+
+    def serial_step(i):
+        a = pinned[i % 16]
+        idx_dev[:a.numel()].copy_(a, non_blocking=True)
+        z.gather(table, idx_dev, bufs[0], n_idx=a.numel(), stream=cur)
+        z.synthetic_compute(cur, comp_blocks, iters, sink)
+        torch.cuda.synchronize()
+
+    for i in range(3):
+        serial_step(i)
+    t0 = time.perf_counter()
+    for i in range(reps):
+        serial_step(i)
+    serial_ms = (time.perf_counter() - t0) / reps * 1e3
+
+    def pipelined(gather_cus):
+        if gather_cus:
+            gs = z.stream_create_cu_mask(list(range(gather_cus)))
+            cs = z.stream_create_cu_mask(list(range(gather_cus, n_cus)))
+            cons = torch.cuda.ExternalStream(cs.cuda_stream)
+        else:
+            gs, cs, cons = None, None, torch.cuda.Stream()
+        pipe = z.pipeline_create(table, max_rows, bufs, gs)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        prev = None
+        for i in range(reps + 1):
+            slot = pipe.submit(lists[i % 16]) if i < reps else None  # producer runs one ahead
+            if prev is not None:
+                pipe.acquire(prev, cons)
+                z.synthetic_compute(cons, comp_blocks, iters, sink)
+                pipe.release(prev, cons)
+            prev = slot
+        cons.synchronize()
+        ms = (time.perf_counter() - t) / reps * 1e3
+        pipe.close()
+        if gs:
+            gs.close()
+            cs.close()
+        return ms
+
+    cases = [{"mode": "one stream, step by step", "ms_per_minibatch": round(serial_ms, 3)},
+             {"mode": "pipeline, 2 buffers, no masks", "ms_per_minibatch": round(pipelined(0), 3)}]
+    for n in (8, 16, 24):
+        cases.append({"mode": f"pipeline, 2 buffers, gather on {n} CUs / compute on {n_cus - n}",
+                      "ms_per_minibatch": round(pipelined(n), 3)})
+    z.synthetic_compute(cur, comp_blocks, iters, sink)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        z.synthetic_compute(cur, comp_blocks, iters, sink)
+    torch.cuda.synchronize()
+    compute_ms = (time.perf_counter() - t0) / reps * 1e3
+    table.close()
+    for c in cases:
+        print(f"# {c}", file=sys.stderr, flush=True)
+    return {"compute_alone_ms": round(compute_ms, 3), "rows_per_minibatch_avg": float(np.mean([a.size for a in lists])),
+            "cases": cases}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -304,7 +380,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep; "
-                         "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning")
+                         "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning; 8 = producer/consumer pipeline")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
     ap.add_argument("--variant", type=int, default=0, help="force a kernel (ablation)")
     ap.add_argument("--sorted", action="store_true", help="ascending index lists (secondary order)")
@@ -344,6 +420,13 @@ def main():
                           "sweep": pts}))
         return
 
+    if args.config == 8:
+        res = run_pipeline(args, z, wl, np, torch, link_peak)
+        print(json.dumps({"metric": "ms per minibatch (list copy + gather + synthetic compute)",
+                          "unit": "ms", "n_gpus": 1, "data": "synthetic", "higher_is_better": False,
+                          "config": {"workload": "config 2 minibatches through the producer->consumer ring"},
+                          "pipeline": res}))
+        return
     if args.config == 7:
         res = run_provisioning(args, z, wl, np, torch, link_peak)
         print(json.dumps({"metric": METRIC, "unit": "GB/s", "n_gpus": 1, "data": "synthetic",

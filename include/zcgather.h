@@ -38,6 +38,7 @@ extern "C" {
 #define ZCG_EALIGN (-6)  /* pointer not aligned to the element size             */
 #define ZCG_EALIAS (-7)  /* output range overlaps the table                     */
 #define ZCG_ERANGE (-8)  /* an index is outside [0, n_rows) (host-side checks)  */
+#define ZCG_EBUSY (-9)   /* pipeline: the next buffer has not been released yet */
 
 /* ---- element types: only the size matters, payload bits are never read -- */
 #define ZCG_F16 1 /* 2-byte elements */
@@ -245,6 +246,38 @@ int zcg_device_cu_count(int device, int* n_cus);
  * (device, 256 floats, CALLER-OWNED). Pure ALU work, asynchronous on `stream`.
  */
 int zcg_synthetic_compute(void* stream, int blocks, int64_t iters, float* sink_dev);
+
+/*
+ * Minibatch pipeline, producer side (Section 3.3: sampler -> producer -> consumer
+ * with alternating GPU buffers and one synchronisation per minibatch). One
+ * process; the producer's gather stream and the caller's consumer stream meet
+ * through events.
+ *   out_bufs      : host array of n_buffers (1..16) device pointers, CALLER-OWNED,
+ *                   each >= max_rows*row_bytes bytes; the ring of output buffers
+ *   gather_stream : stream the list copies and gathers run on (e.g. one from
+ *                   zcg_stream_create_cu_mask); NULL = the pipeline creates its own
+ * The pipeline owns, per buffer, a pinned staging area and a device copy of the
+ * index list (max_rows int64 each). Not thread-safe: one producer thread calls
+ * submit, and acquire/release for a slot follow its submit.
+ */
+typedef struct zcg_pipeline zcg_pipeline;
+int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, void* const* out_bufs,
+                        void* gather_stream, zcg_pipeline** out);
+/*
+ * Producer: copy the list (host, checked: ZCG_ERANGE) to the GPU by DMA and enqueue
+ * the gather into the next buffer of the ring, behind the consumer's release of
+ * that buffer. Returns at once unless the producer is a whole ring ahead of its own
+ * list copies. *slot receives the buffer number. ZCG_EBUSY if the consumer has not
+ * released that buffer since its last use (nothing is enqueued then).
+ */
+int zcg_pipeline_submit(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx, int* slot);
+/* Consumer: make consumer_stream wait for that gather; yields the buffer and its row count. */
+int zcg_pipeline_acquire(zcg_pipeline* p, int slot, void* consumer_stream, void** out_dev,
+                         int64_t* n_rows);
+/* Consumer: work enqueued so far on consumer_stream is the last that reads the buffer. */
+int zcg_pipeline_release(zcg_pipeline* p, int slot, void* consumer_stream);
+/* Waits for the gather stream, frees what the pipeline owns (never the output buffers). */
+int zcg_pipeline_destroy(zcg_pipeline* p);
 
 /* Pinned host scratch for callers without another allocator (staging buffers). */
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr);

@@ -19,7 +19,8 @@ import numpy as np
 from . import build as _build
 
 # status codes / constants (include/zcgather.h)
-OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE = 0, -1, -2, -3, -4, -5, -6, -7, -8
+OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE, EBUSY = (
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9)
 F16, F32 = 1, 2
 ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER, ALLOC_UNCACHED = 0, 1, 2, 4
 VARIANT_AUTO, VARIANT_NAIVE, VARIANT_ROWVEC, VARIANT_ALIGNED, VARIANT_HALFLINE = 0, 1, 2, 3, 4
@@ -36,7 +37,8 @@ EXPORTS = [
     "zcg_gather_ex", "zcg_plan_gather", "zcg_validate_indices", "zcg_cpu_gather_memcpy",
     "zcg_cpu_gather_memcpy_chunked", "zcg_measure_h2d", "zcg_pinned_alloc", "zcg_pinned_free",
     "zcg_version", "zcg_stream_create_cu_mask", "zcg_stream_destroy", "zcg_device_cu_count",
-    "zcg_synthetic_compute",
+    "zcg_synthetic_compute", "zcg_pipeline_create", "zcg_pipeline_submit", "zcg_pipeline_acquire",
+    "zcg_pipeline_release", "zcg_pipeline_destroy",
 ]
 
 
@@ -108,6 +110,11 @@ def load_library() -> ctypes.CDLL:
         "zcg_stream_destroy": (i32, [vp]),
         "zcg_device_cu_count": (i32, [i32, ctypes.POINTER(i32)]),
         "zcg_synthetic_compute": (i32, [vp, i32, i64, vp]),
+        "zcg_pipeline_create": (i32, [vp, i64, i32, ctypes.POINTER(ctypes.c_void_p), vp, pvp]),
+        "zcg_pipeline_submit": (i32, [vp, vp, i64, ctypes.POINTER(i32)]),
+        "zcg_pipeline_acquire": (i32, [vp, i32, vp, pvp, ctypes.POINTER(i64)]),
+        "zcg_pipeline_release": (i32, [vp, i32, vp]),
+        "zcg_pipeline_destroy": (i32, [vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -367,3 +374,44 @@ def stream_destroy(stream: MaskedStream) -> None:
 def synthetic_compute(stream, blocks: int, iters: int, sink_dev) -> None:
     _check(load_library().zcg_synthetic_compute(_stream(stream), blocks, iters, _ptr(sink_dev)),
            "zcg_synthetic_compute")
+
+
+class Pipeline:
+    """zcg_pipeline_*: ring of caller-owned output buffers fed by a gather stream."""
+
+    def __init__(self, table: Table, max_rows: int, out_bufs, gather_stream=None):
+        self._bufs = list(out_bufs)  # keep the tensors alive
+        arr = (ctypes.c_void_p * len(self._bufs))(*[_ptr(b) for b in self._bufs])
+        out = ctypes.c_void_p()
+        _check(load_library().zcg_pipeline_create(table.handle, max_rows, len(self._bufs), arr,
+                                                  _stream(gather_stream), ctypes.byref(out)),
+               "zcg_pipeline_create")
+        self.handle = int(out.value)
+
+    def submit(self, idx_host) -> int:
+        a = _host_idx(idx_host)
+        slot = ctypes.c_int(-1)
+        _check(load_library().zcg_pipeline_submit(self.handle, a.ctypes.data, a.size,
+                                                  ctypes.byref(slot)), "zcg_pipeline_submit")
+        return int(slot.value)
+
+    def acquire(self, slot: int, consumer_stream=None):
+        """Returns (buffer object given at creation, rows gathered into it)."""
+        dev, n = ctypes.c_void_p(), ctypes.c_int64(0)
+        _check(load_library().zcg_pipeline_acquire(self.handle, slot, _stream(consumer_stream),
+                                                   ctypes.byref(dev), ctypes.byref(n)),
+               "zcg_pipeline_acquire")
+        return self._bufs[slot], int(n.value)
+
+    def release(self, slot: int, consumer_stream=None) -> None:
+        _check(load_library().zcg_pipeline_release(self.handle, slot, _stream(consumer_stream)),
+               "zcg_pipeline_release")
+
+    def close(self) -> None:
+        if self.handle:
+            h, self.handle = self.handle, 0
+            _check(load_library().zcg_pipeline_destroy(h), "zcg_pipeline_destroy")
+
+
+def pipeline_create(table: Table, max_rows: int, out_bufs, gather_stream=None) -> Pipeline:
+    return Pipeline(table, max_rows, out_bufs, gather_stream)

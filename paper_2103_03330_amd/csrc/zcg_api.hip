@@ -88,6 +88,7 @@ const char* zcg_strerror(int status) {
     case ZCG_EALIGN: return "pointer not aligned to the element size";
     case ZCG_EALIAS: return "output overlaps the table";
     case ZCG_ERANGE: return "index out of range";
+    case ZCG_EBUSY: return "buffer not released by the consumer";
     default: return "unknown status";
   }
 }

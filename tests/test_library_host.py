@@ -25,7 +25,7 @@ def test_header_and_library_agree_on_exports():
 
 
 def test_status_strings():
-    for code in range(0, -9, -1):
+    for code in range(0, -10, -1):
         assert z.strerror(code) != "unknown status"
     assert z.strerror(-99) == "unknown status"
 
@@ -87,6 +87,27 @@ def test_cpu_baseline_rejects_device_tables_and_bad_lists():
         with pytest.raises(z.ZcgError) as e:
             z.cpu_gather_memcpy(t, np.array([1, 2]), 0x1000, 0x2000)
         assert e.value.status == z.binding.EINVAL
+    finally:
+        t.close()
+
+
+def test_pipeline_argument_checks():
+    lib = z.load_library()
+    t = z.table_from_device(0x100000, 100, 25, "f32")
+    out = ctypes.c_void_p()
+    bufs = (ctypes.c_void_p * 2)(0x900000, 0xA00000)
+    try:
+        assert lib.zcg_pipeline_create(t.handle, 0, 2, bufs, None, ctypes.byref(out)) == z.binding.EINVAL
+        assert lib.zcg_pipeline_create(t.handle, 10, 0, bufs, None, ctypes.byref(out)) == z.binding.EINVAL
+        assert lib.zcg_pipeline_create(t.handle, 10, 17, bufs, None, ctypes.byref(out)) == z.binding.EINVAL
+        assert lib.zcg_pipeline_create(t.handle, 10, 2, None, None, ctypes.byref(out)) == z.binding.EINVAL
+        bad = (ctypes.c_void_p * 2)(0x900000, 0)
+        assert lib.zcg_pipeline_create(t.handle, 10, 2, bad, None, ctypes.byref(out)) == z.binding.EINVAL
+        odd = (ctypes.c_void_p * 2)(0x900002, 0xA00000)
+        assert lib.zcg_pipeline_create(t.handle, 10, 2, odd, None, ctypes.byref(out)) == z.binding.EALIGN
+        assert lib.zcg_pipeline_create(12345, 10, 2, bufs, None, ctypes.byref(out)) == z.binding.EHANDLE
+        assert lib.zcg_pipeline_submit(None, None, 0, None) == z.binding.EINVAL
+        assert lib.zcg_pipeline_destroy(None) == z.binding.EINVAL
     finally:
         t.close()
 
