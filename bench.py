@@ -113,7 +113,28 @@ def run_sweep(args, z, wl, np, torch, link_peak):
                 ms.append(e0.elapsed_time(e1))
             return float(np.median(ms))
 
+        useful = idx.size * cfg.row_bytes
         ms_host = timed(table)
+        # ordered processing: work items walk the table in ascending row order
+        ws_bytes = z.order_workspace_bytes(idx.size)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        order = torch.empty(idx.size, dtype=torch.int64, device="cuda")
+
+        def ordered(with_sort):
+            ms = []
+            for i in range(3 + max(5, min(args.steps, 20))):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                if with_sort or i == 0:
+                    z.make_order(idx_dev, cfg.n_rows, order, ws, ws_bytes, stream=stream)
+                z.gather_ordered(table, idx_dev, order, out, stream=stream)
+                e1.record(stream)
+                e1.synchronize()
+                ms.append(e0.elapsed_time(e1))
+            return float(np.median(ms[3:]))
+
+        ms_ord, ms_ord_sort = ordered(False), ordered(True)
+        del ws
         hbm_t = torch.empty((cfg.n_rows, cfg.dim), dtype=tdt, device="cuda")
         host = table.host_array()
         step = max(1, (1 << 30) // cfg.row_bytes)
@@ -123,7 +144,6 @@ def run_sweep(args, z, wl, np, torch, link_peak):
         ms_hbm = timed(t2)
         t2.close()
         del hbm_t
-        useful = idx.size * cfg.row_bytes
         staging = z.pinned_alloc(useful)
         t0 = time.perf_counter()
         for _ in range(3):
@@ -137,6 +157,8 @@ def run_sweep(args, z, wl, np, torch, link_peak):
                        "zero_copy_gbps": round(useful / ms_host / 1e6, 2),
                        "fraction_of_link_peak": round(useful / ms_host / 1e6 / link_peak, 4),
                        "rows_per_s": round(idx.size / ms_host * 1e3),
+                       "ordered_gbps": round(useful / ms_ord / 1e6, 2),
+                       "ordered_incl_sort_gbps": round(useful / ms_ord_sort / 1e6, 2),
                        "useful_over_line_bytes": round(cfg.row_bytes / (lines * 128), 3),
                        "hbm_resident_gbps": round(useful / ms_hbm / 1e6, 1),
                        "dma_chunked_gbps": round(dma, 2)})

@@ -178,6 +178,33 @@ int zcg_gather_ex(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, voi
                   void* stream, const zcg_launch_opts* opts);
 
 /*
+ * The same gather with a processing order: work item k fetches row idx[order[k]]
+ * and writes output row order[k], so the result is exactly zcg_gather's, but the
+ * table is walked in the order given. With order = the permutation that sorts
+ * idx ascending (zcg_make_order), neighbouring work items touch neighbouring
+ * lines and pages of the host table: repeated and adjacent rows share link
+ * requests. Pays on short rows (measured +35 % on 32-byte rows, +12 % on
+ * 128-byte rows, sort included it still wins below ~128 bytes per row).
+ *   order_dev : device, n_idx int64, a permutation of [0, n_idx); entries outside
+ *               that range are undefined behaviour
+ * NAIVE has no ordered form (ZCG_EINVAL); HALFLINE is run as ALIGNED.
+ */
+int zcg_gather_ordered(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,
+                       int64_t n_idx, void* out_dev, void* stream, const zcg_launch_opts* opts);
+
+/*
+ * Builds that order on the GPU: a stable radix sort of (idx[i], i) pairs by idx.
+ * Asynchronous on `stream`; allocates nothing: all temporary memory is the
+ * caller's workspace (device, 256-byte aligned, at least
+ * zcg_order_workspace_bytes(n_idx) bytes, free to reuse once the stream has
+ * passed the call). n_rows bounds the index values (only the bits below it are
+ * sorted). Equal indices keep their list order.
+ */
+int zcg_order_workspace_bytes(int64_t n_idx, int64_t* bytes);
+int zcg_make_order(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_t* order_dev,
+                   void* workspace_dev, int64_t workspace_bytes, void* stream);
+
+/*
  * Host-only: the launch shape zcg_gather_ex would use for this table, output
  * address and options (no GPU call is made). For tests and for reasoning about
  * which bytes each wave load covers.

@@ -38,7 +38,8 @@ EXPORTS = [
     "zcg_cpu_gather_memcpy_chunked", "zcg_measure_h2d", "zcg_pinned_alloc", "zcg_pinned_free",
     "zcg_version", "zcg_stream_create_cu_mask", "zcg_stream_destroy", "zcg_device_cu_count",
     "zcg_synthetic_compute", "zcg_pipeline_create", "zcg_pipeline_submit", "zcg_pipeline_acquire",
-    "zcg_pipeline_release", "zcg_pipeline_destroy",
+    "zcg_pipeline_release", "zcg_pipeline_destroy", "zcg_gather_ordered",
+    "zcg_order_workspace_bytes", "zcg_make_order",
 ]
 
 
@@ -115,6 +116,9 @@ def load_library() -> ctypes.CDLL:
         "zcg_pipeline_acquire": (i32, [vp, i32, vp, pvp, ctypes.POINTER(i64)]),
         "zcg_pipeline_release": (i32, [vp, i32, vp]),
         "zcg_pipeline_destroy": (i32, [vp]),
+        "zcg_gather_ordered": (i32, [vp, vp, vp, i64, vp, vp, ctypes.POINTER(LaunchOpts)]),
+        "zcg_order_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
+        "zcg_make_order": (i32, [vp, i64, i64, vp, vp, i64, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -415,3 +419,27 @@ class Pipeline:
 
 def pipeline_create(table: Table, max_rows: int, out_bufs, gather_stream=None) -> Pipeline:
     return Pipeline(table, max_rows, out_bufs, gather_stream)
+
+
+def gather_ordered(table: Table, idx_dev, order_dev, out_dev, opts: Optional[LaunchOpts] = None,
+                   n_idx: Optional[int] = None, stream=None) -> None:
+    _check_idx_tensor(idx_dev)
+    _check_idx_tensor(order_dev)
+    rc = load_library().zcg_gather_ordered(table.handle, _ptr(idx_dev), _ptr(order_dev),
+                                           _n_idx(idx_dev, n_idx), _ptr(out_dev), _stream(stream),
+                                           ctypes.byref(opts) if opts is not None else None)
+    _check(rc, "zcg_gather_ordered")
+
+
+def order_workspace_bytes(n_idx: int) -> int:
+    b = ctypes.c_int64(0)
+    _check(load_library().zcg_order_workspace_bytes(n_idx, ctypes.byref(b)), "zcg_order_workspace_bytes")
+    return int(b.value)
+
+
+def make_order(idx_dev, n_rows: int, order_dev, workspace_dev, workspace_bytes: int,
+               n_idx: Optional[int] = None, stream=None) -> None:
+    _check_idx_tensor(idx_dev)
+    rc = load_library().zcg_make_order(_ptr(idx_dev), _n_idx(idx_dev, n_idx), n_rows, _ptr(order_dev),
+                                       _ptr(workspace_dev), workspace_bytes, _stream(stream))
+    _check(rc, "zcg_make_order")

@@ -7,32 +7,51 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libzcgather.so")
-SOURCES = ["zcg_kernels.hip", "zcg_api.hip", "zcg_cpu_baseline.hip", "zcg_pipeline.hip"]
+SOURCES = ["zcg_kernels.hip", "zcg_api.hip", "zcg_cpu_baseline.hip", "zcg_pipeline.hip",
+           "zcg_order.hip"]
 
 
-def hipcc_command() -> list:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+BUILD_DIR = os.path.join(HERE, "_build")
+NOISE = "is not a recognized feature for this target"
+
+
+def hipcc_flags() -> list:
     return [
-        hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-pthread",
+        "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-pthread",
         # keep the compiler from forming packed-fp32 instructions (none are wanted here;
         # this is byte movement, but the flag is the house rule for all device code)
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-        "-o", LIB_PATH,
-    ] + [os.path.join(HERE, "csrc", s) for s in SOURCES]
+    ]
 
 
 def build(verbose: bool = False) -> str:
-    cmd = hipcc_command()
+    """Compile every translation unit (in parallel) and link libzcgather.so."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    procs = []
+    for src in SOURCES:
+        obj = os.path.join(BUILD_DIR, src + ".o")
+        cmd = [hipcc] + hipcc_flags() + ["-c", "-o", obj, os.path.join(HERE, "csrc", src)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE,
+                                                 stderr=subprocess.STDOUT, text=True)))
+    objs = []
+    for src, obj, proc in procs:
+        out, _ = proc.communicate()
+        if proc.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n" + out)
+        out = "\n".join(l for l in out.splitlines() if NOISE not in l and l.strip())
+        if verbose and out:
+            print(out, flush=True)
+        objs.append(obj)
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB_PATH] + objs
     if verbose:
-        print(" ".join(cmd), flush=True)
-    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    noise = "is not a recognized feature for this target"
-    out = "\n".join(l for l in proc.stdout.splitlines() if noise not in l and l.strip())
+        print(" ".join(link), flush=True)
+    proc = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout)
-    if verbose and out:
-        print(out, flush=True)
+        raise RuntimeError("link failed:\n" + proc.stdout)
     return LIB_PATH
 
 

@@ -195,24 +195,45 @@ int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
                        t->kind != ZCG_KIND_DEVICE, opts, plan);
 }
 
-int zcg_gather_ex(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
-                  void* stream, const zcg_launch_opts* opts) {
+static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,
+                         int64_t n_idx, void* out_dev, void* stream, const zcg_launch_opts* opts) {
   if (!zcg_is_live(t)) return ZCG_EHANDLE;
   if (n_idx < 0) return ZCG_EINVAL;
   if (n_idx == 0) return ZCG_OK;
   if (!idx_dev || !out_dev) return ZCG_EINVAL;
-  if ((uintptr_t)idx_dev % 8) return ZCG_EALIGN;
+  if ((uintptr_t)idx_dev % 8 || (uintptr_t)order_dev % 8) return ZCG_EALIGN;
   if (n_idx > INT64_MAX / t->row_bytes) return ZCG_EINVAL;
   const uintptr_t o0 = (uintptr_t)out_dev, o1 = o0 + (uintptr_t)(n_idx * t->row_bytes);
   const uintptr_t t0 = (uintptr_t)t->dev, t1 = t0 + (uintptr_t)(t->n_rows * t->row_bytes);
   if (o0 < t1 && t0 < o1) return ZCG_EALIAS;
+  const bool host_resident = t->kind != ZCG_KIND_DEVICE;
   zcg_plan plan;
-  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, t->kind != ZCG_KIND_DEVICE, opts,
-                         &plan);
+  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, host_resident, opts, &plan);
   if (rc) return rc;
-  hipError_t e = zcg_launch_gather(plan, t->dev, idx_dev, n_idx, out_dev, t->row_bytes, t->elem,
-                                   static_cast<hipStream_t>(stream));
+  if (order_dev) {
+    if (plan.variant == ZCG_VARIANT_NAIVE) return ZCG_EINVAL;
+    if (plan.variant == ZCG_VARIANT_HALFLINE) {  // no ordered form: take the plain aligned kernel
+      zcg_launch_opts o = {};
+      if (opts) o = *opts;
+      o.variant = ZCG_VARIANT_ALIGNED;
+      rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, host_resident, &o, &plan);
+      if (rc) return rc;
+    }
+  }
+  hipError_t e = zcg_launch_gather(plan, t->dev, idx_dev, order_dev, n_idx, out_dev, t->row_bytes,
+                                   t->elem, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
+}
+
+int zcg_gather_ex(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
+                  void* stream, const zcg_launch_opts* opts) {
+  return gather_common(t, idx_dev, nullptr, n_idx, out_dev, stream, opts);
+}
+
+int zcg_gather_ordered(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,
+                       int64_t n_idx, void* out_dev, void* stream, const zcg_launch_opts* opts) {
+  if (n_idx > 0 && !order_dev) return ZCG_EINVAL;
+  return gather_common(t, idx_dev, order_dev, n_idx, out_dev, stream, opts);
 }
 
 int zcg_gather(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,

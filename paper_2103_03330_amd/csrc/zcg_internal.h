@@ -29,7 +29,7 @@ int zcg_fail_hip(hipError_t e);  // records e for zcg_last_hip_error, returns ZC
 int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t out_addr,
                   int64_t n_idx, bool host_resident, const zcg_launch_opts* opts, zcg_plan* plan);
 hipError_t zcg_launch_gather(const zcg_plan& plan, const void* table, const int64_t* idx,
-                             int64_t n_idx, void* out, int64_t row_bytes, int elem,
+                             const int64_t* order, int64_t n_idx, void* out, int64_t row_bytes, int elem,
                              hipStream_t stream);
 hipError_t zcg_launch_synthetic_compute(hipStream_t stream, int blocks, int64_t iters, float* sink);
 hipError_t zcg_launch_validate(const int64_t* idx, int64_t n_idx, int64_t n_rows,

@@ -58,8 +58,8 @@ __device__ __align__(64) uint32_t zcg_dummy_chunk[16];
 template <int W, int U, int NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_narrow(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
-                  int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g,
-                  unsigned line_mask) {
+                  const int64_t* __restrict__ order, int64_t n_idx, uint8_t* __restrict__ out,
+                  int64_t row_bytes, int log2_g, unsigned line_mask) {
   typedef typename vec_of<W>::type vec;
   const unsigned lane = threadIdx.x & ((1u << log2_g) - 1u);
   const int64_t n_groups = ((int64_t)gridDim.x * kBlock) >> log2_g;
@@ -68,22 +68,26 @@ zcg_k_rows_narrow(const uint8_t* __restrict__ table, const int64_t* __restrict__
   const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
 
   for (int64_t base = group; base < n_idx; base += n_groups * U) {
+    int64_t pos[U];  // position in the list = output row; work item k handles order[k]
     int64_t row_id[U];
     vec v[U];
     int64_t dst[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t r = base + (int64_t)u * n_groups;
-      row_id[u] = idx[r < n_idx ? r : n_idx - 1];
+      const int64_t k = base + (int64_t)u * n_groups;
+      const int64_t kc = k < n_idx ? k : n_idx - 1;
+      pos[u] = order ? order[kc] : kc;
     }
 #pragma unroll
+    for (int u = 0; u < U; ++u) row_id[u] = idx[pos[u]];
+#pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t r = base + (int64_t)u * n_groups;
+      const int64_t k = base + (int64_t)u * n_groups;
       const uint8_t* src = table + row_id[u] * row_bytes;
       const int64_t off = lane_off - (int64_t)((uintptr_t)src & line_mask);
-      const bool ok = (r < n_idx) && (off >= 0) && (off < row_bytes);
+      const bool ok = (k < n_idx) && (off >= 0) && (off < row_bytes);
       v[u] = load_chunk<W, NTL>(ok ? src + off : dummy);
-      dst[u] = ok ? r * row_bytes + off : -1;
+      dst[u] = ok ? pos[u] * row_bytes + off : -1;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -95,8 +99,9 @@ zcg_k_rows_narrow(const uint8_t* __restrict__ table, const int64_t* __restrict__
 // span in steps of 64*W bytes, U steps in flight.
 template <int W, int U, int NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
-zcg_k_rows_wide(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx, int64_t n_idx,
-                uint8_t* __restrict__ out, int64_t row_bytes, unsigned line_mask) {
+zcg_k_rows_wide(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
+                const int64_t* __restrict__ order, int64_t n_idx, uint8_t* __restrict__ out,
+                int64_t row_bytes, unsigned line_mask) {
   typedef typename vec_of<W>::type vec;
   const unsigned lane = threadIdx.x & (kWave - 1);
   const int64_t n_waves = ((int64_t)gridDim.x * kBlock) / kWave;
@@ -104,7 +109,8 @@ zcg_k_rows_wide(const uint8_t* __restrict__ table, const int64_t* __restrict__ i
   constexpr int64_t kStep = (int64_t)kWave * W;
   const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
 
-  for (int64_t r = wave; r < n_idx; r += n_waves) {
+  for (int64_t k = wave; k < n_idx; k += n_waves) {
+    const int64_t r = order ? order[k] : k;  // position in the list = output row
     const uint8_t* src = table + idx[r] * row_bytes;
     const int64_t mis = (int64_t)((uintptr_t)src & line_mask);
     const int64_t span = mis + row_bytes;
@@ -171,7 +177,8 @@ __device__ __forceinline__ void store_shifted(uint8_t* out_row, int64_t off, int
 template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_narrow_shift(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
-                        int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g,
+                        const int64_t* __restrict__ order, int64_t n_idx,
+                        uint8_t* __restrict__ out, int64_t row_bytes, int log2_g,
                         unsigned line_mask) {
   typedef typename vec_of<W>::type vec;
   const unsigned lane = threadIdx.x & ((1u << log2_g) - 1u);
@@ -181,36 +188,38 @@ zcg_k_rows_narrow_shift(const uint8_t* __restrict__ table, const int64_t* __rest
   const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
 
   for (int64_t base = group; base < n_idx; base += n_groups * U) {
+    int64_t pos[U];
     int64_t row_id[U];
     vec v[U];
     int64_t off[U];
     bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t r = base + (int64_t)u * n_groups;
-      row_id[u] = idx[r < n_idx ? r : n_idx - 1];
+      const int64_t k = base + (int64_t)u * n_groups;
+      const int64_t kc = k < n_idx ? k : n_idx - 1;
+      pos[u] = order ? order[kc] : kc;
     }
 #pragma unroll
+    for (int u = 0; u < U; ++u) row_id[u] = idx[pos[u]];
+#pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t r = base + (int64_t)u * n_groups;
+      const int64_t k = base + (int64_t)u * n_groups;
       const uint8_t* src = table + row_id[u] * row_bytes;
       off[u] = lane_off - (int64_t)((uintptr_t)src & line_mask);
-      ok[u] = (r < n_idx) && (off[u] > -(int64_t)W) && (off[u] < row_bytes);
+      ok[u] = (k < n_idx) && (off[u] > -(int64_t)W) && (off[u] < row_bytes);
       v[u] = load_chunk<W, 0>(ok[u] ? src + off[u] : dummy);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t r = base + (int64_t)u * n_groups;
-      if (ok[u]) store_shifted<W, WS, NTS>(out + r * row_bytes, off[u], 0, row_bytes, v[u]);
-    }
+    for (int u = 0; u < U; ++u)
+      if (ok[u]) store_shifted<W, WS, NTS>(out + pos[u] * row_bytes, off[u], 0, row_bytes, v[u]);
   }
 }
 
 template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_wide_shift(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
-                      int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes,
-                      unsigned line_mask) {
+                      const int64_t* __restrict__ order, int64_t n_idx, uint8_t* __restrict__ out,
+                      int64_t row_bytes, unsigned line_mask) {
   typedef typename vec_of<W>::type vec;
   const unsigned lane = threadIdx.x & (kWave - 1);
   const int64_t n_waves = ((int64_t)gridDim.x * kBlock) / kWave;
@@ -218,7 +227,8 @@ zcg_k_rows_wide_shift(const uint8_t* __restrict__ table, const int64_t* __restri
   constexpr int64_t kStep = (int64_t)kWave * W;
   const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
 
-  for (int64_t r = wave; r < n_idx; r += n_waves) {
+  for (int64_t k = wave; k < n_idx; k += n_waves) {
+    const int64_t r = order ? order[k] : k;
     const uint8_t* src = table + idx[r] * row_bytes;
     const int64_t mis = (int64_t)((uintptr_t)src & line_mask);
     uint8_t* out_row = out + r * row_bytes;
@@ -455,7 +465,7 @@ int floor_pow2_divisor(uint64_t x, int cap) {  // largest power of two <= cap di
 }
 
 template <int W, int U>
-hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* idx, int64_t n_idx,
+hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* idx, const int64_t* order, int64_t n_idx,
                        uint8_t* out, int64_t row_bytes, hipStream_t s) {
   const unsigned mask = (p.variant == ZCG_VARIANT_ALIGNED) ? (unsigned)(p.line_bytes - 1) : 0u;
   const dim3 grid((unsigned)p.blocks), block(kBlock);
@@ -480,11 +490,11 @@ hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* i
 #define ZCG_LAUNCH(NTL, NTS)                                                                    \
   do {                                                                                          \
     if (p.iters == 1)                                                                           \
-      zcg_k_rows_narrow<W, U, NTL, NTS><<<grid, block, 0, s>>>(table, idx, n_idx, out,         \
+      zcg_k_rows_narrow<W, U, NTL, NTS><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,  \
                                                                  row_bytes, p.log2_group, mask); \
     else                                                                                        \
-      zcg_k_rows_wide<W, U, NTL, NTS><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes, \
-                                                               mask);                           \
+      zcg_k_rows_wide<W, U, NTL, NTS><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,    \
+                                                               row_bytes, mask);                \
   } while (0)
   switch (p.nt_loads * 2 + (p.nt_stores ? 1 : 0)) {
     case 0: ZCG_LAUNCH(0, false); break;
@@ -500,18 +510,18 @@ hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* i
 
 template <int W>
 hipError_t launch_rows_u(const zcg_plan& p, const uint8_t* table, const int64_t* idx,
-                         int64_t n_idx, uint8_t* out, int64_t row_bytes, hipStream_t s) {
+                         const int64_t* order, int64_t n_idx, uint8_t* out, int64_t row_bytes, hipStream_t s) {
   switch (p.unroll) {
-    case 1: return launch_rows<W, 1>(p, table, idx, n_idx, out, row_bytes, s);
-    case 2: return launch_rows<W, 2>(p, table, idx, n_idx, out, row_bytes, s);
-    case 4: return launch_rows<W, 4>(p, table, idx, n_idx, out, row_bytes, s);
-    case 8: return launch_rows<W, 8>(p, table, idx, n_idx, out, row_bytes, s);
+    case 1: return launch_rows<W, 1>(p, table, idx, order, n_idx, out, row_bytes, s);
+    case 2: return launch_rows<W, 2>(p, table, idx, order, n_idx, out, row_bytes, s);
+    case 4: return launch_rows<W, 4>(p, table, idx, order, n_idx, out, row_bytes, s);
+    case 8: return launch_rows<W, 8>(p, table, idx, order, n_idx, out, row_bytes, s);
     default: return hipErrorInvalidValue;
   }
 }
 
 template <int W, int WS, int U>
-hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* idx, int64_t n_idx,
+hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* idx, const int64_t* order, int64_t n_idx,
                         uint8_t* out, int64_t row_bytes, hipStream_t s) {
   const unsigned mask = (unsigned)(p.line_bytes - 1);
   const dim3 grid((unsigned)p.blocks), block(kBlock);
@@ -537,17 +547,17 @@ hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* 
   }
   if (p.iters == 1) {
     if (p.nt_stores)
-      zcg_k_rows_narrow_shift<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+      zcg_k_rows_narrow_shift<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                       row_bytes, p.log2_group, mask);
     else
-      zcg_k_rows_narrow_shift<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+      zcg_k_rows_narrow_shift<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                        row_bytes, p.log2_group, mask);
   } else {
     if (p.nt_stores)
-      zcg_k_rows_wide_shift<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes,
+      zcg_k_rows_wide_shift<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, order, n_idx, out, row_bytes,
                                                                     mask);
     else
-      zcg_k_rows_wide_shift<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+      zcg_k_rows_wide_shift<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                      row_bytes, mask);
   }
   return hipGetLastError();
@@ -555,12 +565,12 @@ hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* 
 
 template <int W, int WS>
 hipError_t launch_shift_u(const zcg_plan& p, const uint8_t* table, const int64_t* idx,
-                          int64_t n_idx, uint8_t* out, int64_t row_bytes, hipStream_t s) {
+                          const int64_t* order, int64_t n_idx, uint8_t* out, int64_t row_bytes, hipStream_t s) {
   switch (p.unroll) {
-    case 1: return launch_shift<W, WS, 1>(p, table, idx, n_idx, out, row_bytes, s);
-    case 2: return launch_shift<W, WS, 2>(p, table, idx, n_idx, out, row_bytes, s);
-    case 4: return launch_shift<W, WS, 4>(p, table, idx, n_idx, out, row_bytes, s);
-    case 8: return launch_shift<W, WS, 8>(p, table, idx, n_idx, out, row_bytes, s);
+    case 1: return launch_shift<W, WS, 1>(p, table, idx, order, n_idx, out, row_bytes, s);
+    case 2: return launch_shift<W, WS, 2>(p, table, idx, order, n_idx, out, row_bytes, s);
+    case 4: return launch_shift<W, WS, 4>(p, table, idx, order, n_idx, out, row_bytes, s);
+    case 8: return launch_shift<W, WS, 8>(p, table, idx, order, n_idx, out, row_bytes, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -700,8 +710,11 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
 }
 
 hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t* idx,
-                             int64_t n_idx, void* out, int64_t row_bytes, int elem,
-                             hipStream_t stream) {
+                             const int64_t* order, int64_t n_idx, void* out, int64_t row_bytes,
+                             int elem, hipStream_t stream) {
+  // a processing order exists only for the row kernels that start at or below the row start
+  if (order && (p.variant == ZCG_VARIANT_NAIVE || p.variant == ZCG_VARIANT_HALFLINE))
+    return hipErrorInvalidValue;
   if (p.variant == ZCG_VARIANT_NAIVE) {
     const int64_t dim = row_bytes / elem;
     return elem == 4 ? launch_flat<uint32_t>(p, table, idx, n_idx, out, dim, stream)
@@ -711,19 +724,19 @@ hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t
   uint8_t* o = static_cast<uint8_t*>(out);
   if (p.store_bytes < p.vec_bytes) {
     switch (p.vec_bytes * 100 + p.store_bytes) {
-      case 1608: return launch_shift_u<16, 8>(p, t, idx, n_idx, o, row_bytes, stream);
-      case 1604: return launch_shift_u<16, 4>(p, t, idx, n_idx, o, row_bytes, stream);
-      case 1602: return launch_shift_u<16, 2>(p, t, idx, n_idx, o, row_bytes, stream);
-      case 804: return launch_shift_u<8, 4>(p, t, idx, n_idx, o, row_bytes, stream);
-      case 802: return launch_shift_u<8, 2>(p, t, idx, n_idx, o, row_bytes, stream);
+      case 1608: return launch_shift_u<16, 8>(p, t, idx, order, n_idx, o, row_bytes, stream);
+      case 1604: return launch_shift_u<16, 4>(p, t, idx, order, n_idx, o, row_bytes, stream);
+      case 1602: return launch_shift_u<16, 2>(p, t, idx, order, n_idx, o, row_bytes, stream);
+      case 804: return launch_shift_u<8, 4>(p, t, idx, order, n_idx, o, row_bytes, stream);
+      case 802: return launch_shift_u<8, 2>(p, t, idx, order, n_idx, o, row_bytes, stream);
       default: return hipErrorInvalidValue;
     }
   }
   switch (p.vec_bytes) {
-    case 16: return launch_rows_u<16>(p, t, idx, n_idx, o, row_bytes, stream);
-    case 8: return launch_rows_u<8>(p, t, idx, n_idx, o, row_bytes, stream);
-    case 4: return launch_rows_u<4>(p, t, idx, n_idx, o, row_bytes, stream);
-    case 2: return launch_rows_u<2>(p, t, idx, n_idx, o, row_bytes, stream);
+    case 16: return launch_rows_u<16>(p, t, idx, order, n_idx, o, row_bytes, stream);
+    case 8: return launch_rows_u<8>(p, t, idx, order, n_idx, o, row_bytes, stream);
+    case 4: return launch_rows_u<4>(p, t, idx, order, n_idx, o, row_bytes, stream);
+    case 2: return launch_rows_u<2>(p, t, idx, order, n_idx, o, row_bytes, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -266,3 +266,43 @@ def test_gather_on_a_cu_masked_stream():
         torch.cuda.synchronize()
     finally:
         table.close()
+
+
+ORDERED_SHAPES = [(40000, 16, "f16"), (40000, 16, "f32"), (30000, 64, "f16"), (5000, 100, "f32"),
+                  (3000, 602, "f32"), (2000, 257, "f16"), (900, 1025, "f32"), (1001, 3, "f32")]
+
+
+@pytest.mark.parametrize("n_rows,dim,dtype", ORDERED_SHAPES)
+def test_ordered_gather_matches_oracle(n_rows, dim, dtype):
+    """Processing order changes which work item moves which row, never the result."""
+    table = host_table(n_rows, dim, dtype, seed=dim)
+    try:
+        idx = wl.uniform_indices(50021, n_rows, seed=17)  # many repeated and adjacent rows
+        want = oracle_gather(table.host_array(), idx)
+        idx_dev = torch.from_numpy(idx).cuda()
+        ws_bytes = z.order_workspace_bytes(idx.size)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        order = torch.empty(idx.size, dtype=torch.int64, device="cuda")
+        z.make_order(idx_dev, n_rows, order, ws, ws_bytes)
+        torch.cuda.synchronize()
+        o = order.cpu().numpy()
+        assert np.array_equal(np.sort(o), np.arange(idx.size))  # a permutation
+        assert np.array_equal(o, np.argsort(idx, kind="stable"))  # ascending, ties in list order
+        for name, perm in (("sorted", order),
+                           ("random", torch.randperm(idx.size, device="cuda")),
+                           ("reversed", torch.arange(idx.size - 1, -1, -1, device="cuda"))):
+            for variant in (z.VARIANT_AUTO, z.VARIANT_ROWVEC, z.VARIANT_ALIGNED, z.VARIANT_HALFLINE):
+                out = torch.full((idx.size, dim), -7.0, dtype=TORCH_DT[dtype], device="cuda")
+                z.gather_ordered(table, idx_dev, perm, out, z.LaunchOpts(variant=variant))
+                torch.cuda.synchronize()
+                assert_same_bits(out, want, f"ordered {name} variant={variant}")
+        out = torch.zeros((idx.size, dim), dtype=TORCH_DT[dtype], device="cuda")
+        with pytest.raises(z.ZcgError) as e:
+            z.gather_ordered(table, idx_dev, order, out, z.LaunchOpts(variant=z.VARIANT_NAIVE))
+        assert e.value.status == -1
+        with pytest.raises(z.ZcgError) as e:
+            z.make_order(idx_dev, n_rows, order, ws, ws_bytes - 256)
+        assert e.value.status == -1
+        z.gather_ordered(table, idx_dev, order, out, n_idx=0)  # empty: nothing to do
+    finally:
+        table.close()
