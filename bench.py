@@ -519,6 +519,44 @@ def main():
     avg_kernel_ms = float(kern_ms.mean())
     achieved = avg_rows * rb / (avg_kernel_ms * 1e-3) / 1e9
 
+    # --- side legs on the same inputs (outside the timed region)
+    def event_ms(fn, reps=10):
+        fn()
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            e1.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return float(np.median(ms))
+
+    # shader-issued ceiling: the same kernel reading consecutive rows (identity list)
+    n_seq = min(build_info["n_rows"], max(max_n, (256 << 20) // rb))
+    seq_idx = torch.arange(n_seq, dtype=torch.int64, device="cuda")
+    seq_out = torch.empty((n_seq, cfg.dim), dtype=torch_dt, device="cuda")
+    stream_gbps = n_seq * rb / event_ms(lambda: z.gather(table, seq_idx, seq_out, stream=stream)) / 1e6
+    del seq_idx, seq_out
+    # the index list's own host-to-device copy (the paper sends it by DMA before the gather)
+    pin_idx = torch.from_numpy(lists[0]).pin_memory()
+    idx_h2d_us = event_ms(lambda: idx_dev[0].copy_(pin_idx, non_blocking=True)) * 1e3
+    # the same table resident in HBM (the paper's all-in-GPU comparison), if it fits comfortably
+    hbm_gbps = None
+    if build_info["n_rows"] * rb <= 64e9:
+        hbm_t = torch.empty((build_info["n_rows"], cfg.dim), dtype=torch_dt, device="cuda")
+        host = table.host_array()
+        chunk = max(1, (1 << 30) // rb)
+        for lo in range(0, build_info["n_rows"], chunk):
+            hbm_t[lo:lo + chunk].copy_(torch.from_numpy(host[lo:lo + chunk]))
+        t_hbm = z.table_from_device(hbm_t, build_info["n_rows"], cfg.dim, cfg.dtype)
+        tot_ms = sum(event_ms(lambda b=b: z.gather(t_hbm, idx_dev[b], outs[0], n_idx=lists[b].size,
+                                                   stream=stream), reps=5) for b in range(min(4, n_batches)))
+        hbm_gbps = sum(lists[b].size for b in range(min(4, n_batches))) * rb / tot_ms / 1e6
+        t_hbm.close()
+        del hbm_t
+
     prof = read_profile_traffic(f"gather_cfg{args.config}_counters.txt")
     traffic = None
     if "link_read_bytes_per_row" in prof:
@@ -544,7 +582,10 @@ def main():
         "fraction_of_link_peak": round(value / link_peak, 4),
         "rows_per_s": round(rows / wall),
         "link": {"measured_h2d_gbps": round(link_peak, 2), "nominal_gbps": nominal, "name": link_name,
-                 "fraction_of_nominal": round(value / nominal, 4) if nominal else None},
+                 "fraction_of_nominal": round(value / nominal, 4) if nominal else None,
+                 "shader_stream_read_gbps": round(stream_gbps, 2),
+                 "index_list_h2d_us": round(idx_h2d_us, 1)},
+        "hbm_resident_table_gbps": round(hbm_gbps, 1) if hbm_gbps else None,
         "per_step_kernel_gbps": {"min": round(float(per_step_gbps.min()), 2),
                                  "median": round(float(np.median(per_step_gbps)), 2),
                                  "max": round(float(per_step_gbps.max()), 2)},

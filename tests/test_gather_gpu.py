@@ -306,3 +306,55 @@ def test_ordered_gather_matches_oracle(n_rows, dim, dtype):
         z.gather_ordered(table, idx_dev, order, out, n_idx=0)  # empty: nothing to do
     finally:
         table.close()
+
+
+def test_seeded_random_shapes_knobs_and_offsets():
+    """40 seeded random combinations of row size, dtype, list length, base offsets, kernel and
+    launch knobs (ordered or not) against the oracle; one long list to exercise grid striding."""
+    rng = np.random.default_rng(20210303)
+    cases = []
+    for _ in range(40):
+        dtype = "f16" if rng.random() < 0.4 else "f32"
+        elem = 2 if dtype == "f16" else 4
+        dim = int(rng.choice([1, 2, 3, 5, 8, 16, 31, 64, 100, 127, 128, 129, 255, 300, 602, 1000, 2051]))
+        n_rows = int(rng.integers(1, 4000))
+        n_idx = int(rng.choice([1, 2, 63, 64, 65, 1000, 4097, 30000]))
+        cases.append((dtype, elem, dim, n_rows, n_idx))
+    cases.append(("f32", 4, 2, 100_000, 3_000_000))  # 8-byte rows, long list
+    for ci, (dtype, elem, dim, n_rows, n_idx) in enumerate(cases):
+        t_off = int(rng.integers(0, 9)) * elem  # table base off by 0..8 elements
+        o_off = int(rng.integers(0, 9)) * elem
+        backing = z.alloc_table(n_rows + 1, dim + 16, dtype)  # room for the shifted view
+        try:
+            wl.fill_table_ptr(backing.host_ptr, n_rows + 1, dim + 16, dtype, seed=ci, mode=wl.FILL_RAW_BITS)
+            flat = backing.host_array().reshape(-1)
+            sub = np.ascontiguousarray(flat[t_off // elem: t_off // elem + n_rows * dim].reshape(n_rows, dim))
+            view = z.table_from_device(backing.device_ptr + t_off, n_rows, dim, dtype)
+            idx = rng.integers(0, n_rows, n_idx)
+            want = oracle_gather(sub, idx)
+            idx_dev = torch.from_numpy(idx).cuda()
+            buf = torch.zeros(n_idx * dim + 32, dtype=TORCH_DT[dtype], device="cuda")
+            out = buf[o_off // elem: o_off // elem + n_idx * dim].view(n_idx, dim)
+            opts = z.LaunchOpts(variant=int(rng.integers(0, 5)), unroll=int(rng.choice([0, 1, 2, 4, 8])),
+                                line_bytes=int(rng.choice([0, 32, 64, 128, 256])),
+                                vec_bytes=int(rng.choice([0, 4, 8, 16])) if elem == 4 else int(rng.choice([0, 2, 8, 16])),
+                                group_lanes=int(rng.choice([0, 1, 8, 64])),
+                                shifted_stores=int(rng.integers(0, 3)), nt_loads=int(rng.integers(0, 4)),
+                                nt_stores=int(rng.integers(0, 3)),
+                                max_blocks=int(rng.choice([0, 1, 7, 300])))
+            what = f"case {ci}: {dtype} dim={dim} rows={n_rows} n_idx={n_idx} t_off={t_off} o_off={o_off} " \
+                   f"opts={[getattr(opts, f) for f, _ in opts._fields_]}"
+            if rng.random() < 0.4 and opts.variant != z.VARIANT_NAIVE:
+                perm = torch.randperm(n_idx, device="cuda")
+                z.gather_ordered(view, idx_dev, perm, out, opts)
+                what += " ordered"
+            else:
+                z.gather_ex(view, idx_dev, out, opts)
+            torch.cuda.synchronize()
+            assert_same_bits(out, want, what)
+            guard_lo, guard_hi = buf[: o_off // elem], buf[o_off // elem + n_idx * dim:]
+            assert not bool(guard_lo.view(torch.int16 if elem == 2 else torch.int32).any()), what
+            assert not bool(guard_hi.view(torch.int16 if elem == 2 else torch.int32).any()), what
+            view.close()
+        finally:
+            backing.close()
