@@ -314,7 +314,16 @@ def run_provisioning(args, z, wl, np, torch, link_peak):
         mc.close()
         print(f"# {overlap[-1]}", file=sys.stderr, flush=True)
     table.close()
-    return {"gather_vs_cu_share": share_curve, "gather_vs_grid_size": grid_curve,
+    rtt_us = z.measure_host_read_latency(20000)
+    full = share_curve[-1]["gbps"]
+    lines_per_s = full * 1e9 / rb * 4  # a 400-byte row costs four 128-byte lines
+    littles = {"host_read_round_trip_us": round(rtt_us, 3),
+               "lines_per_s_at_full_rate": round(lines_per_s),
+               "lines_in_flight": round(lines_per_s * rtt_us * 1e-6),
+               "bytes_in_flight": round(lines_per_s * rtt_us * 1e-6 * 128),
+               "note": "Little's law with the unloaded round trip: a lower bound on what must be in flight"}
+    print(f"# {littles}", file=sys.stderr, flush=True)
+    return {"littles_law": littles, "gather_vs_cu_share": share_curve, "gather_vs_grid_size": grid_curve,
             "overlap": {"gather_alone_ms": round(gather_alone, 3), "compute_alone_ms": round(compute_alone, 3),
                         "compute_blocks": comp_blocks, "compute_iters": iters, "cases": overlap}}
 

@@ -307,6 +307,15 @@ int zcg_pipeline_release(zcg_pipeline* p, int slot, void* consumer_stream);
 /* Waits for the gather stream, frees what the pipeline owns (never the output buffers). */
 int zcg_pipeline_destroy(zcg_pipeline* p);
 
+/*
+ * Round-trip time of one read of mapped host memory from a GPU lane: a single
+ * lane follows `hops` (16 .. 2^22) dependent loads through a random cycle laid
+ * over a 256 MiB mapped buffer, one slot per page. With the measured request
+ * rate this gives the number of reads in flight (Little's law, the sizing
+ * argument of Section 3.2.2). SYNCHRONOUS; allocates and frees its buffers.
+ */
+int zcg_measure_host_read_latency(int device, int64_t hops, double* microseconds);
+
 /* Pinned host scratch for callers without another allocator (staging buffers). */
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr);
 int zcg_pinned_free(void* host_ptr);

@@ -39,7 +39,7 @@ EXPORTS = [
     "zcg_version", "zcg_stream_create_cu_mask", "zcg_stream_destroy", "zcg_device_cu_count",
     "zcg_synthetic_compute", "zcg_pipeline_create", "zcg_pipeline_submit", "zcg_pipeline_acquire",
     "zcg_pipeline_release", "zcg_pipeline_destroy", "zcg_gather_ordered",
-    "zcg_order_workspace_bytes", "zcg_make_order",
+    "zcg_order_workspace_bytes", "zcg_make_order", "zcg_measure_host_read_latency",
 ]
 
 
@@ -119,6 +119,7 @@ def load_library() -> ctypes.CDLL:
         "zcg_gather_ordered": (i32, [vp, vp, vp, i64, vp, vp, ctypes.POINTER(LaunchOpts)]),
         "zcg_order_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
         "zcg_make_order": (i32, [vp, i64, i64, vp, vp, i64, vp]),
+        "zcg_measure_host_read_latency": (i32, [i32, i64, ctypes.POINTER(ctypes.c_double)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -443,3 +444,11 @@ def make_order(idx_dev, n_rows: int, order_dev, workspace_dev, workspace_bytes: 
     rc = load_library().zcg_make_order(_ptr(idx_dev), _n_idx(idx_dev, n_idx), n_rows, _ptr(order_dev),
                                        _ptr(workspace_dev), workspace_bytes, _stream(stream))
     _check(rc, "zcg_make_order")
+
+
+def measure_host_read_latency(hops: int = 20000, device: int = 0) -> float:
+    """Round-trip time in microseconds of one dependent read of mapped host memory."""
+    us = ctypes.c_double(0.0)
+    _check(load_library().zcg_measure_host_read_latency(device, hops, ctypes.byref(us)),
+           "zcg_measure_host_read_latency")
+    return float(us.value)

@@ -352,6 +352,52 @@ int zcg_synthetic_compute(void* stream, int blocks, int64_t iters, float* sink_d
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
 }
 
+int zcg_measure_host_read_latency(int device, int64_t hops, double* microseconds) {
+  if (device < 0 || hops < 16 || hops > (1 << 22) || !microseconds) return ZCG_EINVAL;
+  *microseconds = 0.0;
+  DeviceScope scope(device);
+  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
+  // a random cycle over 2^16 slots, one slot per 4 KiB page of a 256 MiB mapped host buffer
+  constexpr int64_t kSlots = 1 << 16, kStrideWords = 4096 / 8;
+  uint64_t *host = nullptr, *dev_view = nullptr, *result = nullptr;
+  hipStream_t s = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  float ms = 0.f;
+  hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&host), (size_t)kSlots * 4096,
+                               hipHostMallocMapped | hipHostMallocCoherent);
+  if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void**>(&dev_view), host, 0);
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&result), sizeof(uint64_t));
+  if (e == hipSuccess) e = hipStreamCreate(&s);
+  if (e == hipSuccess) e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e == hipSuccess) {
+    std::vector<uint64_t> perm((size_t)kSlots);
+    for (int64_t i = 0; i < kSlots; ++i) perm[(size_t)i] = (uint64_t)i;
+    uint64_t x = 0x9E3779B97F4A7C15ull;
+    for (int64_t i = kSlots - 1; i > 0; --i) {  // Fisher-Yates with a xorshift stream
+      x ^= x << 13; x ^= x >> 7; x ^= x << 17;
+      std::swap(perm[(size_t)i], perm[(size_t)(x % (uint64_t)(i + 1))]);
+    }
+    for (int64_t i = 0; i < kSlots; ++i)  // perm order becomes one cycle through all slots
+      host[perm[(size_t)i] * kStrideWords] = perm[(size_t)((i + 1) % kSlots)];
+    e = zcg_launch_chase(s, dev_view, kStrideWords, 64, result);  // warm-up
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = zcg_launch_chase(s, dev_view, kStrideWords, hops, result);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  }
+  if (e1) (void)hipEventDestroy(e1);
+  if (e0) (void)hipEventDestroy(e0);
+  if (s) (void)hipStreamDestroy(s);
+  if (result) (void)hipFree(result);
+  if (host) (void)hipHostFree(host);
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  *microseconds = (double)ms * 1e3 / (double)hops;
+  return ZCG_OK;
+}
+
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr) {
   if (bytes <= 0 || !host_ptr) return ZCG_EINVAL;
   *host_ptr = nullptr;

@@ -458,6 +458,15 @@ zcg_k_synthetic_compute(int64_t iters, float* __restrict__ sink) {
   atomicAdd(&sink[threadIdx.x], a);
 }
 
+// One lane follows a chain of dependent loads: next = chain[next * stride].
+__global__ void zcg_k_chase(const uint64_t* __restrict__ chain, int64_t stride_words, int64_t hops,
+                            uint64_t* __restrict__ result) {
+  uint64_t p = 0;
+  for (int64_t i = 0; i < hops; ++i)
+    p = *(const volatile uint64_t __attribute__((address_space(1)))*)(chain + p * stride_words);
+  *result = p;
+}
+
 int floor_pow2_divisor(uint64_t x, int cap) {  // largest power of two <= cap dividing x
   int w = cap;
   while (w > 1 && (x % (uint64_t)w) != 0) w >>= 1;
@@ -742,6 +751,12 @@ hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t
     case 2: return launch_rows_u<2>(p, t, idx, order, n_idx, o, row_bytes, stream);
     default: return hipErrorInvalidValue;
   }
+}
+
+hipError_t zcg_launch_chase(hipStream_t stream, const uint64_t* chain, int64_t stride_words,
+                            int64_t hops, uint64_t* result) {
+  zcg_k_chase<<<dim3(1), dim3(1), 0, stream>>>(chain, stride_words, hops, result);
+  return hipGetLastError();
 }
 
 hipError_t zcg_launch_synthetic_compute(hipStream_t stream, int blocks, int64_t iters, float* sink) {

@@ -358,3 +358,9 @@ def test_seeded_random_shapes_knobs_and_offsets():
             view.close()
         finally:
             backing.close()
+
+
+def test_link_probes_give_sane_numbers():
+    rtt = z.measure_host_read_latency(4000)
+    assert 0.2 < rtt < 50.0  # microseconds per dependent read of mapped host memory
+    assert 5.0 < z.measure_h2d(64 << 20, 3) < 200.0  # GB/s
