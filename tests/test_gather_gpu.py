@@ -364,3 +364,24 @@ def test_link_probes_give_sane_numbers():
     rtt = z.measure_host_read_latency(4000)
     assert 0.2 < rtt < 50.0  # microseconds per dependent read of mapped host memory
     assert 5.0 < z.measure_h2d(64 << 20, 3) < 200.0  # GB/s
+
+
+@pytest.mark.parametrize("flags", [z.ALLOC_DEFAULT, z.ALLOC_NONCOHERENT, z.ALLOC_UNCACHED])
+def test_host_updates_between_gathers_are_seen(flags):
+    """The table lives in host memory: rows the CPU rewrites after one gather has finished must be
+    what the next gather returns, for every kernel (vector caches and the scalar cache alike)."""
+    n_rows, dim = 3000, 602
+    table = host_table(n_rows, dim, "f32", seed=3, flags=flags)
+    try:
+        host = table.host_array()
+        idx = wl.uniform_indices(9000, n_rows, seed=8)
+        idx_dev = torch.from_numpy(idx).cuda()
+        for variant in ALL_VARIANTS:
+            for round_ in range(3):
+                out = torch.zeros((idx.size, dim), dtype=torch.float32, device="cuda")
+                z.gather_variant(table, idx_dev, out, variant)
+                torch.cuda.synchronize()
+                assert_same_bits(out, oracle_gather(host, idx), f"variant {variant} round {round_}")
+                host[:] = host[::-1].copy() if round_ % 2 == 0 else host * np.float32(0.5)
+    finally:
+        table.close()
