@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libzcgather.so")
-SOURCES = ["zcg_kernels.hip", "zcg_api.hip", "zcg_cpu_baseline.hip", "zcg_pipeline.hip",
+SOURCES = ["zcg_kernels.hip", "zcg_plan.hip", "zcg_api.hip", "zcg_cpu_baseline.hip", "zcg_pipeline.hip",
            "zcg_order.hip"]
 
 

@@ -467,12 +467,6 @@ __global__ void zcg_k_chase(const uint64_t* __restrict__ chain, int64_t stride_w
   *result = p;
 }
 
-int floor_pow2_divisor(uint64_t x, int cap) {  // largest power of two <= cap dividing x
-  int w = cap;
-  while (w > 1 && (x % (uint64_t)w) != 0) w >>= 1;
-  return w;
-}
-
 template <int W, int U>
 hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* idx, const int64_t* order, int64_t n_idx,
                        uint8_t* out, int64_t row_bytes, hipStream_t s) {
@@ -609,117 +603,6 @@ hipError_t launch_flat(const zcg_plan& p, const void* table, const int64_t* idx,
 }
 
 }  // namespace
-
-int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t out_addr,
-                  int64_t n_idx, bool host_resident, const zcg_launch_opts* opts, zcg_plan* plan) {
-  zcg_launch_opts o = {};
-  if (opts) o = *opts;
-  if (row_bytes <= 0 || (elem != 2 && elem != 4) || row_bytes % elem != 0 || n_idx < 0 || !plan)
-    return ZCG_EINVAL;
-  if (table_addr % (uintptr_t)elem != 0 || out_addr % (uintptr_t)elem != 0) return ZCG_EALIGN;
-
-  // defaults
-  int variant = o.variant;
-  int line = o.line_bytes ? o.line_bytes : 128;
-  int unroll = o.unroll ? o.unroll : (host_resident ? 2 : 4);
-  int vec_cap = o.vec_bytes ? o.vec_bytes : 16;
-  if (!o.vec_bytes && host_resident) {
-    // Measured over the host link: 8-byte lanes (a wave pass = 512 bytes = 4 lines) are as
-    // fast or slightly faster than 16-byte lanes for every row longer than a line; rows of
-    // at most one line do best with 16-byte lanes.
-    const int pref = row_bytes <= 128 ? 16 : 8;
-    vec_cap = pref < elem ? elem : pref;
-  }
-  // HBM-resident tables (measured): a grid large enough for one row per group without
-  // striding and non-temporal table loads are worth up to +19 % (1 KiB rows).
-  int max_blocks = o.max_blocks ? o.max_blocks
-                                : (!host_resident ? 65536 : (row_bytes > 128 ? 2048 : 8192));
-  const int ntl = o.nt_loads == 1 ? 1 : (o.nt_loads == 3 ? 2 : (o.nt_loads == 0 && !host_resident ? 1 : 0));
-  const int nts = o.nt_stores == 2 ? 0 : 1;                // default: non-temporal stores
-  if (variant < 0 || variant >= ZCG_VARIANT_COUNT) return ZCG_EINVAL;
-  if (line != 32 && line != 64 && line != 128 && line != 256) return ZCG_EINVAL;
-  if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return ZCG_EINVAL;
-  if (vec_cap != 2 && vec_cap != 4 && vec_cap != 8 && vec_cap != 16) return ZCG_EINVAL;
-  if (max_blocks < 1 || o.nt_loads < 0 || o.nt_loads > 3 || o.nt_stores < 0 || o.nt_stores > 2)
-    return ZCG_EINVAL;
-  if (vec_cap < elem || o.shifted_stores < 0 || o.shifted_stores > 2) return ZCG_EINVAL;
-  int min_lg = 0;
-  if (o.group_lanes) {
-    if (o.group_lanes < 1 || o.group_lanes > kWave || (o.group_lanes & (o.group_lanes - 1)))
-      return ZCG_EINVAL;
-    while ((1 << min_lg) < o.group_lanes) ++min_lg;
-  } else if (host_resident) {
-    // Measured: over the host link one row per wave-wide load instruction is the
-    // fastest and the least sensitive to grid size and unrolling; rows of at most
-    // one line do slightly better 16 lanes wide on a larger grid.
-    min_lg = row_bytes > 128 ? 6 : 4;
-  }
-
-  // Widest access that keeps every chunk of every row aligned at both ends.
-  int w = floor_pow2_divisor((uint64_t)row_bytes, vec_cap);
-  w = floor_pow2_divisor((uint64_t)table_addr, w);
-  w = floor_pow2_divisor((uint64_t)out_addr, w);
-
-  // HALFLINE moves dwords through the scalar path: needs 4-byte granularity everywhere.
-  const bool half_ok = (w >= 4);
-  if (variant == ZCG_VARIANT_HALFLINE && !half_ok) variant = ZCG_VARIANT_ALIGNED;
-  if (variant == ZCG_VARIANT_HALFLINE) line = 128;
-  if (variant == ZCG_VARIANT_AUTO) {
-    // Rows shorter than a line, or made of whole lines on a line-aligned base,
-    // need no realignment (the paper's applicability rule, end of Section 3.2.1).
-    const bool whole_lines = (row_bytes % line == 0) && (table_addr % (uintptr_t)line == 0);
-    variant = (row_bytes < line || whole_lines) ? ZCG_VARIANT_ROWVEC : ZCG_VARIANT_ALIGNED;
-    // Long unaligned rows over the host link: one half-line read per ~8+ lines is a net gain
-    // (measured +2...4 % on 1,032...2,408-byte rows with 8- or 16-byte lanes); on short rows
-    // it is a loss, with 4-byte lanes it is neutral.
-    if (variant == ZCG_VARIANT_ALIGNED && host_resident && row_bytes >= 1024 &&
-        (w >= 8 || (w >= 4 && vec_cap >= 8 && o.shifted_stores != 2)))
-      variant = ZCG_VARIANT_HALFLINE, line = 128;
-  }
-
-  plan->variant = variant;
-  plan->line_bytes = line;
-  plan->unroll = unroll;
-  plan->nt_loads = ntl;
-  plan->nt_stores = nts;
-
-  int64_t want_blocks;
-  if (variant == ZCG_VARIANT_NAIVE) {
-    plan->vec_bytes = elem;
-    plan->store_bytes = elem;
-    plan->log2_group = 0;
-    plan->iters = 1;
-    plan->unroll = 1;
-    const int64_t total = n_idx * (row_bytes / elem);
-    want_blocks = (total + kBlock - 1) / kBlock;
-  } else {
-    // ALIGNED loads sit at line-aligned positions, so they can stay vec_cap wide when the
-    // rows or bases are less aligned than that; only the stores drop to w (shifted stores).
-    const bool line_mapped = variant == ZCG_VARIANT_ALIGNED || variant == ZCG_VARIANT_HALFLINE;
-    int wl = w;
-    if (line_mapped && w < vec_cap && vec_cap >= 8 && o.shifted_stores != 2)
-      wl = vec_cap;
-    plan->vec_bytes = wl;
-    plan->store_bytes = w;
-    const int64_t worst_span = row_bytes + (line_mapped ? line - w : 0);
-    const int64_t chunks = (worst_span + wl - 1) / wl;
-    int lg = 0;
-    while (lg < 6 && ((int64_t)1 << lg) < chunks) ++lg;
-    if (lg < min_lg) lg = min_lg;
-    plan->log2_group = lg;
-    plan->iters = (int)((chunks + ((int64_t)1 << lg) - 1) >> lg);
-    if (plan->iters == 1) {
-      const int64_t groups = (n_idx + unroll - 1) / unroll;
-      want_blocks = ((groups << lg) + kBlock - 1) / kBlock;
-    } else {
-      plan->log2_group = 6;
-      want_blocks = (n_idx * kWave + kBlock - 1) / kBlock;
-    }
-  }
-  if (want_blocks < 1) want_blocks = 1;
-  plan->blocks = (int)(want_blocks < max_blocks ? want_blocks : max_blocks);
-  return ZCG_OK;
-}
 
 hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t* idx,
                              const int64_t* order, int64_t n_idx, void* out, int64_t row_bytes,
