@@ -366,7 +366,7 @@ def test_link_probes_give_sane_numbers():
     assert 5.0 < z.measure_h2d(64 << 20, 3) < 200.0  # GB/s
 
 
-@pytest.mark.parametrize("flags", [z.ALLOC_DEFAULT, z.ALLOC_NONCOHERENT, z.ALLOC_UNCACHED])
+@pytest.mark.parametrize("flags", [z.ALLOC_DEFAULT, z.ALLOC_NONCOHERENT])
 def test_host_updates_between_gathers_are_seen(flags):
     """The table lives in host memory: rows the CPU rewrites after one gather has finished must be
     what the next gather returns, for every kernel (vector caches and the scalar cache alike)."""
