@@ -87,7 +87,7 @@ typedef struct zcg_launch_opts {
   int vec_bytes;   /* cap on bytes per lane access: 2, 4, 8 or 16                      */
   int group_lanes; /* lanes given to one row, a power of two up to 64; raised to what
                       the row needs. 64 = one row per wave-wide load instruction       */
-  int shifted_stores; /* ALIGNED with rows or bases less aligned than vec_bytes: 1 (and the
+  int shifted_stores; /* ALIGNED / HALFLINE with rows or bases less aligned than vec_bytes: 1 (and the
                       default) keeps the loads vec_bytes wide at line-aligned positions and
                       writes with narrower / unaligned stores; 2 narrows the loads instead.
                       With wide loads, up to vec_bytes-1 bytes next to a row end, inside
@@ -165,7 +165,10 @@ int zcg_unregister_table(zcg_table* t);
  *             element size (16-byte alignment enables the widest accesses),
  *             must not overlap the table (ZCG_EALIAS).
  * The caller keeps idx_dev, out_dev and the table alive until the stream has
- * passed the kernel. n_idx == 0 succeeds without a launch.
+ * passed the kernel. n_idx == 0 succeeds without a launch. The table must not
+ * change while a gather that reads it runs; rows the host rewrites after a
+ * gather has completed are seen by every later gather (the GPU's caches, the
+ * scalar cache included, are invalidated when a kernel starts).
  */
 int zcg_gather(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
                void* stream);
