@@ -573,6 +573,10 @@ def main():
                    "hbm_write_bytes": round(prof.get("hbm_write_bytes_per_row", rb) * avg_rows),
                    "source": f"profiles/gather_cfg{args.config}_counters.txt (rocprofv3 --pmc)"}
 
+    from paper_2103_03330_amd import link_model
+    model_bytes = float(np.mean([link_model.link_bytes_per_row(rb, a, table.device_ptr,
+                                                                halfline=plan["variant"] == z.VARIANT_HALFLINE)
+                                 for a in lists[:4]]))
     result = {
         "metric": METRIC, "value": round(value, 3), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 4),
@@ -600,6 +604,11 @@ def main():
                                  "max": round(float(per_step_gbps.max()), 2)},
         "roofline": {"bound": "host_link", "achieved": round(achieved, 3), "peak": round(link_peak, 2),
                      "unit": "GB/s", "frac": round(achieved / link_peak, 4), "traffic": traffic,
+                     "traffic_model": {"link_read_bytes": round(model_bytes * avg_rows),
+                                       "link_bytes_per_row": round(model_bytes, 1),
+                                       "useful_over_link": round(rb / model_bytes, 4),
+                                       "what": "whole 128 B lines spanned by each row (64 B half lines "
+                                               "for row ends under HALFLINE)"},
                      "kernel_ms_avg": round(avg_kernel_ms, 4),
                      "peak_is": "measured pinned hipMemcpyAsync host->device (1 GiB, median of 10)",
                      "algorithmic_bytes_per_row": rb,
