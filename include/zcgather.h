@@ -31,7 +31,7 @@ extern "C" {
 /* ---- status codes ------------------------------------------------------ */
 #define ZCG_OK 0
 #define ZCG_EINVAL (-1)  /* null pointer, non-positive size, bad option value   */
-#define ZCG_EDTYPE (-2)  /* dtype is not one of ZCG_F16 / ZCG_F32               */
+#define ZCG_EDTYPE (-2)  /* dtype is not one of the ZCG_* element types          */
 #define ZCG_EHANDLE (-3) /* not a live table handle (never made, or destroyed)  */
 #define ZCG_EHIP (-4)    /* a HIP runtime call failed; see zcg_last_hip_error() */
 #define ZCG_ENOMEM (-5)  /* host allocation failed                              */
@@ -41,8 +41,10 @@ extern "C" {
 #define ZCG_EBUSY (-9)   /* pipeline: the next buffer has not been released yet */
 
 /* ---- element types: only the size matters, payload bits are never read -- */
-#define ZCG_F16 1 /* 2-byte elements */
-#define ZCG_F32 2 /* 4-byte elements */
+#define ZCG_F16 1 /* 2-byte elements (fp16, bf16, int16)         */
+#define ZCG_F32 2 /* 4-byte elements (fp32, int32)               */
+#define ZCG_B8 3  /* 1-byte elements (int8, fp8 feature tables)  */
+#define ZCG_B64 4 /* 8-byte elements (fp64, int64)               */
 
 /* ---- allocation flags for zcg_alloc_table ------------------------------ */
 #define ZCG_ALLOC_DEFAULT 0u     /* pinned, mapped, coherent (fine-grained)         */
@@ -84,7 +86,7 @@ typedef struct zcg_launch_opts {
   int nt_loads;    /* 1: non-temporal table loads, 2: plain loads, 3: system scope;
                       default: plain for host tables, non-temporal for HBM tables      */
   int nt_stores;   /* 1: non-temporal output stores, 2: plain stores                   */
-  int vec_bytes;   /* cap on bytes per lane access: 2, 4, 8 or 16                      */
+  int vec_bytes;   /* cap on bytes per lane access: 1, 2, 4, 8 or 16 (>= element size)  */
   int group_lanes; /* lanes given to one row, a power of two up to 64; raised to what
                       the row needs. 64 = one row per wave-wide load instruction       */
   int shifted_stores; /* ALIGNED / HALFLINE with rows or bases less aligned than vec_bytes: 1 (and the

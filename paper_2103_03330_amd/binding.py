@@ -21,14 +21,14 @@ from . import build as _build
 # status codes / constants (include/zcgather.h)
 OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE, EBUSY = (
     0, -1, -2, -3, -4, -5, -6, -7, -8, -9)
-F16, F32 = 1, 2
+F16, F32, B8, B64 = 1, 2, 3, 4
 ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER, ALLOC_UNCACHED = 0, 1, 2, 4
 VARIANT_AUTO, VARIANT_NAIVE, VARIANT_ROWVEC, VARIANT_ALIGNED, VARIANT_HALFLINE = 0, 1, 2, 3, 4
 VARIANT_NAMES = {VARIANT_AUTO: "auto", VARIANT_NAIVE: "naive", VARIANT_ROWVEC: "rowvec",
                  VARIANT_ALIGNED: "aligned", VARIANT_HALFLINE: "halfline"}
-_DTYPES = {"f16": F16, "f32": F32, F16: F16, F32: F32}
-_ELEM = {F16: 2, F32: 4}
-_NP = {F16: np.float16, F32: np.float32}
+_DTYPES = {"f16": F16, "f32": F32, "i8": B8, "f64": B64, F16: F16, F32: F32, B8: B8, B64: B64}
+_ELEM = {F16: 2, F32: 4, B8: 1, B64: 8}
+_NP = {F16: np.float16, F32: np.float32, B8: np.int8, B64: np.float64}
 
 EXPORTS = [
     "zcg_strerror", "zcg_last_hip_error", "zcg_register_table", "zcg_alloc_table",

@@ -20,6 +20,8 @@ thread_local int t_last_hip = 0;
 int elem_of(int dtype) {
   if (dtype == ZCG_F16) return 2;
   if (dtype == ZCG_F32) return 4;
+  if (dtype == ZCG_B8) return 1;
+  if (dtype == ZCG_B64) return 8;
   return 0;
 }
 

@@ -24,6 +24,7 @@ template <> struct vec_of<16> { typedef u32x4 type; };
 template <> struct vec_of<8> { typedef u32x2 type; };
 template <> struct vec_of<4> { typedef uint32_t type; };
 template <> struct vec_of<2> { typedef uint16_t type; };
+template <> struct vec_of<1> { typedef uint8_t type; };
 
 // Load modes: 0 plain, 1 non-temporal (nt), 2 system scope (sc0 sc1).
 template <int W, int LM>
@@ -612,8 +613,12 @@ hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t
     return hipErrorInvalidValue;
   if (p.variant == ZCG_VARIANT_NAIVE) {
     const int64_t dim = row_bytes / elem;
-    return elem == 4 ? launch_flat<uint32_t>(p, table, idx, n_idx, out, dim, stream)
-                     : launch_flat<uint16_t>(p, table, idx, n_idx, out, dim, stream);
+    switch (elem) {
+      case 8: return launch_flat<uint64_t>(p, table, idx, n_idx, out, dim, stream);
+      case 4: return launch_flat<uint32_t>(p, table, idx, n_idx, out, dim, stream);
+      case 2: return launch_flat<uint16_t>(p, table, idx, n_idx, out, dim, stream);
+      default: return launch_flat<uint8_t>(p, table, idx, n_idx, out, dim, stream);
+    }
   }
   const uint8_t* t = static_cast<const uint8_t*>(table);
   uint8_t* o = static_cast<uint8_t*>(out);
@@ -624,6 +629,8 @@ hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t
       case 1602: return launch_shift_u<16, 2>(p, t, idx, order, n_idx, o, row_bytes, stream);
       case 804: return launch_shift_u<8, 4>(p, t, idx, order, n_idx, o, row_bytes, stream);
       case 802: return launch_shift_u<8, 2>(p, t, idx, order, n_idx, o, row_bytes, stream);
+      case 1601: return launch_shift_u<16, 1>(p, t, idx, order, n_idx, o, row_bytes, stream);
+      case 801: return launch_shift_u<8, 1>(p, t, idx, order, n_idx, o, row_bytes, stream);
       default: return hipErrorInvalidValue;
     }
   }
@@ -632,6 +639,7 @@ hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t
     case 8: return launch_rows_u<8>(p, t, idx, order, n_idx, o, row_bytes, stream);
     case 4: return launch_rows_u<4>(p, t, idx, order, n_idx, o, row_bytes, stream);
     case 2: return launch_rows_u<2>(p, t, idx, order, n_idx, o, row_bytes, stream);
+    case 1: return launch_rows_u<1>(p, t, idx, order, n_idx, o, row_bytes, stream);
     default: return hipErrorInvalidValue;
   }
 }

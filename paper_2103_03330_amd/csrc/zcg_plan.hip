@@ -22,7 +22,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
                   int64_t n_idx, bool host_resident, const zcg_launch_opts* opts, zcg_plan* plan) {
   zcg_launch_opts o = {};
   if (opts) o = *opts;
-  if (row_bytes <= 0 || (elem != 2 && elem != 4) || row_bytes % elem != 0 || n_idx < 0 || !plan)
+  if (row_bytes <= 0 || (elem != 1 && elem != 2 && elem != 4 && elem != 8) || row_bytes % elem != 0 || n_idx < 0 || !plan)
     return ZCG_EINVAL;
   if (table_addr % (uintptr_t)elem != 0 || out_addr % (uintptr_t)elem != 0) return ZCG_EALIGN;
 
@@ -47,7 +47,8 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   if (variant < 0 || variant >= ZCG_VARIANT_COUNT) return ZCG_EINVAL;
   if (line != 32 && line != 64 && line != 128 && line != 256) return ZCG_EINVAL;
   if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return ZCG_EINVAL;
-  if (vec_cap != 2 && vec_cap != 4 && vec_cap != 8 && vec_cap != 16) return ZCG_EINVAL;
+  if (vec_cap != 1 && vec_cap != 2 && vec_cap != 4 && vec_cap != 8 && vec_cap != 16)
+    return ZCG_EINVAL;
   if (max_blocks < 1 || o.nt_loads < 0 || o.nt_loads > 3 || o.nt_stores < 0 || o.nt_stores > 2)
     return ZCG_EINVAL;
   if (vec_cap < elem || o.shifted_stores < 0 || o.shifted_stores > 2) return ZCG_EINVAL;

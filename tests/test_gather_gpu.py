@@ -13,7 +13,7 @@ z = pytest.importorskip("paper_2103_03330_amd")
 
 ALL_VARIANTS = [z.VARIANT_AUTO, z.VARIANT_NAIVE, z.VARIANT_ROWVEC, z.VARIANT_ALIGNED,
                 z.VARIANT_HALFLINE]
-TORCH_DT = {"f16": torch.float16, "f32": torch.float32}
+TORCH_DT = {"f16": torch.float16, "f32": torch.float32, "i8": torch.int8, "f64": torch.float64}
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -33,7 +33,7 @@ def host_table(n_rows, dim, dtype, seed, mode=wl.FILL_UNIFORM, flags=z.ALLOC_DEF
 def run_gather(table, idx_np, dtype, opts=None, out=None):
     idx_dev = torch.from_numpy(np.ascontiguousarray(idx_np, dtype=np.int64)).cuda()
     if out is None:
-        out = torch.full((len(idx_np), table.dim), -7.0, dtype=TORCH_DT[dtype], device="cuda")
+        out = torch.full((len(idx_np), table.dim), -7, dtype=TORCH_DT[dtype], device="cuda")
     z.gather_ex(table, idx_dev, out, opts, n_idx=len(idx_np))
     torch.cuda.synchronize()
     return out
@@ -56,6 +56,9 @@ SHAPES = [
     # rows inside one half line (32 B, 64 B), straddling halves (48 B, 80 B, 200 B), 2-byte odd
     (4000, 16, "f16"), (4000, 16, "f32"), (3000, 12, "f32"), (3000, 20, "f32"), (2500, 50, "f32"),
     (2500, 98, "f16"), (1300, 99, "f16"), (700, 1023, "f32"),
+    # 1-byte (int8 / fp8) and 8-byte elements: odd byte rows, sub-line, long, line multiples
+    (3000, 1, "i8"), (3000, 37, "i8"), (2500, 100, "i8"), (2000, 401, "i8"), (900, 2049, "i8"),
+    (2000, 512, "i8"), (1500, 1, "f64"), (1500, 50, "f64"), (800, 301, "f64"),
 ]
 
 
@@ -74,7 +77,8 @@ def test_all_variants_match_oracle(n_rows, dim, dtype):
         table.close()
 
 
-@pytest.mark.parametrize("dim,dtype", [(100, "f32"), (602, "f32"), (257, "f16"), (2050, "f16")])
+@pytest.mark.parametrize("dim,dtype", [(100, "f32"), (602, "f32"), (257, "f16"), (2050, "f16"),
+                                       (401, "i8"), (301, "f64")])
 def test_launch_knobs_do_not_change_the_result(dim, dtype):
     n_rows = 3001
     table = host_table(n_rows, dim, dtype, seed=dim)
@@ -86,12 +90,14 @@ def test_launch_knobs_do_not_change_the_result(dim, dtype):
                 for line in (32, 64, 128, 256):
                     o = z.LaunchOpts(variant=variant, unroll=unroll, line_bytes=line)
                     assert_same_bits(run_gather(table, idx, dtype, o), want, f"u{unroll} l{line}")
-            for vec in (2, 4, 8, 16):
+            for vec in (1, 2, 4, 8, 16):
                 if vec < table.elem_bytes:
                     continue
                 o = z.LaunchOpts(variant=variant, vec_bytes=vec, nt_loads=1, nt_stores=2)
                 assert_same_bits(run_gather(table, idx, dtype, o), want, f"vec{vec}")
             for vec in (8, 16):  # narrow loads instead of shifted stores
+                if vec < table.elem_bytes:
+                    continue
                 o = z.LaunchOpts(variant=variant, vec_bytes=vec, shifted_stores=2, group_lanes=16)
                 assert_same_bits(run_gather(table, idx, dtype, o), want, f"noshift vec{vec}")
             # one block only: the grid-stride loop does all the work

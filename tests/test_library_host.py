@@ -37,6 +37,7 @@ def test_argument_checks_run_before_any_gpu_call():
         (lambda: z.register_table(a, 0, 4, "f32"), z.binding.EINVAL),
         (lambda: z.register_table(a, 4, -1, "f32"), z.binding.EINVAL),
         (lambda: z.register_table(a, 4, 4, 7), z.binding.EDTYPE),
+        (lambda: z.register_table(a.ctypes.data + 4, 2, 3, "f64"), z.binding.EALIGN),
         (lambda: z.register_table(a.ctypes.data + 2, 4, 3, "f32"), z.binding.EALIGN),
         (lambda: z.alloc_table(4, 4, "f32", flags=64), z.binding.EINVAL),
         (lambda: z.alloc_table(2 ** 62, 2 ** 10, "f32"), z.binding.EINVAL),
@@ -148,13 +149,19 @@ def test_plan_picks_width_group_and_variant():
     assert (p["vec_bytes"], p["store_bytes"]) == (8, 8)
     p = plan(3, "f16")
     assert p["vec_bytes"] == 2
+    p = plan(401, "i8")  # odd byte rows: byte-granular stores under 16-byte line-aligned loads
+    assert (p["variant"], p["vec_bytes"], p["store_bytes"]) == (z.VARIANT_ALIGNED, 16, 1)
+    p = plan(37, "i8")
+    assert (p["variant"], p["vec_bytes"]) == (z.VARIANT_ROWVEC, 1)
+    p = plan(50, "f64")
+    assert (p["vec_bytes"], p["store_bytes"]) == (16, 16)
     p = plan(100, "f32", variant=z.VARIANT_NAIVE)
     assert (p["variant"], p["vec_bytes"]) == (z.VARIANT_NAIVE, 4)
     p = plan(100, "f32", max_blocks=7)
     assert p["blocks"] == 7
     p = plan(100, "f32", n_idx=3)
     assert p["blocks"] == 1
-    for bad in (dict(unroll=3), dict(line_bytes=48), dict(vec_bytes=2), dict(variant=5),
+    for bad in (dict(unroll=3), dict(line_bytes=48), dict(vec_bytes=2), dict(vec_bytes=3), dict(variant=5),
                 dict(nt_loads=4), dict(shifted_stores=3)):
         with pytest.raises(z.ZcgError):
             plan(100, "f32", **bad)

@@ -81,8 +81,8 @@ def default_threads() -> int:
         return max(1, os.cpu_count() or 1)
 
 
-_ELEM = {"f16": 2, "f32": 4}
-_NP = {"f16": np.float16, "f32": np.float32}
+_ELEM = {"f16": 2, "f32": 4, "i8": 1, "f64": 8}
+_NP = {"f16": np.float16, "f32": np.float32, "i8": np.int8, "f64": np.float64}
 
 
 def elem_bytes(dtype: str) -> int:

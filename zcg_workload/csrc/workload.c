@@ -54,7 +54,7 @@ static inline uint16_t half_from_k11(uint32_t k) {
 
 /*
  * Fill a row-major [n_rows x dim] table in place.
- *   elem_bytes 4: fp32, elem_bytes 2: fp16.
+ *   elem_bytes 4: fp32, 2: fp16, 1: int8, 8: fp64.
  *   mode 0: uniform on [-1,1): fp32 takes the top 24 bits k of the stream value
  *           and stores (k - 2^23) * 2^-23; fp16 takes the top 11 bits k and
  *           stores (k - 2^10) * 2^-10. Both are exactly representable.
@@ -65,7 +65,8 @@ static inline uint16_t half_from_k11(uint32_t k) {
  */
 int zcgw_fill_table(void* dst, int64_t n_rows, int64_t dim, int elem_bytes, uint64_t seed,
                     int mode, int n_threads) {
-  if (!dst || n_rows < 0 || dim <= 0 || (elem_bytes != 2 && elem_bytes != 4) ||
+  if (!dst || n_rows < 0 || dim <= 0 ||
+      (elem_bytes != 1 && elem_bytes != 2 && elem_bytes != 4 && elem_bytes != 8) ||
       (mode != 0 && mode != 1))
     return -1;
   const int64_t total = n_rows * dim;
@@ -82,12 +83,33 @@ int zcgw_fill_table(void* dst, int64_t n_rows, int64_t dim, int elem_bytes, uint
         p[i] = (uint32_t)z;
       }
     }
-  } else {
+  } else if (elem_bytes == 2) {
     uint16_t* p = (uint16_t*)dst;
 #pragma omp parallel for schedule(static) num_threads(n_threads)
     for (int64_t i = 0; i < total; ++i) {
       uint64_t z = stream_at(seed, (uint64_t)i);
       p[i] = (mode == 0) ? half_from_k11((uint32_t)(z >> 53)) : (uint16_t)z;
+    }
+  } else if (elem_bytes == 1) {
+    /* mode 0: int8 uniform on [-128, 127] from the top 8 bits; mode 1: the low byte */
+    uint8_t* p = (uint8_t*)dst;
+#pragma omp parallel for schedule(static) num_threads(n_threads)
+    for (int64_t i = 0; i < total; ++i) {
+      uint64_t z = stream_at(seed, (uint64_t)i);
+      p[i] = (mode == 0) ? (uint8_t)(z >> 56) : (uint8_t)z;
+    }
+  } else {
+    /* mode 0: fp64 (k - 2^52) * 2^-52 from the top 53 bits k; mode 1: all 64 bits */
+    uint64_t* p = (uint64_t*)dst;
+#pragma omp parallel for schedule(static) num_threads(n_threads)
+    for (int64_t i = 0; i < total; ++i) {
+      uint64_t z = stream_at(seed, (uint64_t)i);
+      if (mode == 0) {
+        double f = (double)((int64_t)(z >> 11) - ((int64_t)1 << 52)) * 0x1p-52;
+        memcpy(&p[i], &f, 8);
+      } else {
+        p[i] = z;
+      }
     }
   }
   return 0;
