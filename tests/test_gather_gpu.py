@@ -320,8 +320,8 @@ def test_seeded_random_shapes_knobs_and_offsets():
     rng = np.random.default_rng(20210303)
     cases = []
     for _ in range(40):
-        dtype = "f16" if rng.random() < 0.4 else "f32"
-        elem = 2 if dtype == "f16" else 4
+        dtype = str(rng.choice(["f16", "f32", "f32", "i8", "f64"]))
+        elem = {"i8": 1, "f16": 2, "f32": 4, "f64": 8}[dtype]
         dim = int(rng.choice([1, 2, 3, 5, 8, 16, 31, 64, 100, 127, 128, 129, 255, 300, 602, 1000, 2051]))
         n_rows = int(rng.integers(1, 4000))
         n_idx = int(rng.choice([1, 2, 63, 64, 65, 1000, 4097, 30000]))
@@ -343,7 +343,7 @@ def test_seeded_random_shapes_knobs_and_offsets():
             out = buf[o_off // elem: o_off // elem + n_idx * dim].view(n_idx, dim)
             opts = z.LaunchOpts(variant=int(rng.integers(0, 5)), unroll=int(rng.choice([0, 1, 2, 4, 8])),
                                 line_bytes=int(rng.choice([0, 32, 64, 128, 256])),
-                                vec_bytes=int(rng.choice([0, 4, 8, 16])) if elem == 4 else int(rng.choice([0, 2, 8, 16])),
+                                vec_bytes=int(rng.choice([0] + [v for v in (1, 2, 4, 8, 16) if v >= elem])),
                                 group_lanes=int(rng.choice([0, 1, 8, 64])),
                                 shifted_stores=int(rng.integers(0, 3)), nt_loads=int(rng.integers(0, 4)),
                                 nt_stores=int(rng.integers(0, 3)),
@@ -359,8 +359,9 @@ def test_seeded_random_shapes_knobs_and_offsets():
             torch.cuda.synchronize()
             assert_same_bits(out, want, what)
             guard_lo, guard_hi = buf[: o_off // elem], buf[o_off // elem + n_idx * dim:]
-            assert not bool(guard_lo.view(torch.int16 if elem == 2 else torch.int32).any()), what
-            assert not bool(guard_hi.view(torch.int16 if elem == 2 else torch.int32).any()), what
+            as_int = {1: torch.int8, 2: torch.int16, 4: torch.int32, 8: torch.int64}[elem]
+            assert not bool(guard_lo.view(as_int).any()), what
+            assert not bool(guard_hi.view(as_int).any()), what
             view.close()
         finally:
             backing.close()
