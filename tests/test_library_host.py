@@ -219,3 +219,31 @@ def test_aligned_loads_touch_each_line_once(golden):
     assert requests(0, 4, 32) == golden["example_requests_naive"]
     assert requests(src % line, 4, 32) == golden["example_requests_shifted"]
     assert requests(src % line, 16, 64) == golden["example_requests_shifted"]
+
+
+def test_handle_registry_is_thread_safe():
+    """Handles are created, queried and destroyed from many threads at once."""
+    import threading
+
+    lib = z.load_library()
+    errors = []
+
+    def worker(seed):
+        try:
+            for i in range(300):
+                t = z.table_from_device(0x100000 + 4096 * (seed * 1000 + i), 10 + i, 4, "f32")
+                assert t.row_bytes == 16 and lib.zcg_table_n_rows(t.handle) == 10 + i
+                p = z.plan_gather(t, 100, 0x7E0000000000)
+                assert p["blocks"] >= 1
+                h = t.handle
+                t.close()
+                assert lib.zcg_table_n_rows(h) == 0
+        except Exception as e:  # noqa: BLE001
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(s,)) for s in range(8)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors[:3]
