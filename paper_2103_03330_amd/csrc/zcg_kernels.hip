@@ -1,4 +1,4 @@
-// Gather kernels for gfx950 and the host-side plan that picks their launch shape.
+// Gather kernels for gfx950 and their launchers (the launch shape is chosen in zcg_plan.hip).
 //
 // The work is pure data movement over the host link (table in mapped host
 // memory) or HBM (device-resident table): no MFMA, no LDS. What matters is
