@@ -352,12 +352,15 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
         z.synthetic_compute(cur, comp_blocks, iters, sink)
         torch.cuda.synchronize()
 
-    for i in range(3):
-        serial_step(i)
-    t0 = time.perf_counter()
-    for i in range(reps):
-        serial_step(i)
-    serial_ms = (time.perf_counter() - t0) / reps * 1e3
+    only = args.pipeline_mode  # run one mode only (for kernel-trace profiles)
+    serial_ms = None
+    if only in ("all", "serial"):
+        for i in range(3):
+            serial_step(i)
+        t0 = time.perf_counter()
+        for i in range(reps):
+            serial_step(i)
+        serial_ms = (time.perf_counter() - t0) / reps * 1e3
 
     def pipelined(gather_cus):
         if gather_cus:
@@ -385,11 +388,15 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
             cs.close()
         return ms
 
-    cases = [{"mode": "one stream, step by step", "ms_per_minibatch": round(serial_ms, 3)},
-             {"mode": "pipeline, 2 buffers, no masks", "ms_per_minibatch": round(pipelined(0), 3)}]
+    cases = []
+    if serial_ms is not None:
+        cases.append({"mode": "one stream, step by step", "ms_per_minibatch": round(serial_ms, 3)})
+    if only in ("all", "nomask"):
+        cases.append({"mode": "pipeline, 2 buffers, no masks", "ms_per_minibatch": round(pipelined(0), 3)})
     for n in (8, 16, 24):
-        cases.append({"mode": f"pipeline, 2 buffers, gather on {n} CUs / compute on {n_cus - n}",
-                      "ms_per_minibatch": round(pipelined(n), 3)})
+        if only in ("all", f"mask{n}"):
+            cases.append({"mode": f"pipeline, 2 buffers, gather on {n} CUs / compute on {n_cus - n}",
+                          "ms_per_minibatch": round(pipelined(n), 3)})
     z.synthetic_compute(cur, comp_blocks, iters, sink)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -417,6 +424,9 @@ def main():
     ap.add_argument("--sorted", action="store_true", help="ascending index lists (secondary order)")
     ap.add_argument("--max-table-gb", type=float, default=200.0)
     ap.add_argument("--no-baselines", action="store_true", help="skip the CPU legs (for profiling)")
+    ap.add_argument("--pipeline-mode", default="all",
+                    choices=["all", "serial", "nomask", "mask8", "mask16", "mask24"],
+                    help="config 8: run one mode only (for kernel-trace profiles)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy, as the known-size reference for counters")
     args = ap.parse_args()
