@@ -15,3 +15,4 @@ from .binding import (  # noqa: F401
     last_hip_error, load_library, measure_h2d, measure_host_read_latency, pipeline_create, pinned_alloc, pinned_free, plan_gather,
     register_table, strerror, table_from_device, unregister_table, validate_indices, version,
 )
+from .unified import UnifiedTensor, to_unified  # noqa: F401,E402
