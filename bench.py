@@ -101,13 +101,13 @@ def run_sweep(args, z, wl, np, torch, link_peak):
 
         def timed(t):
             for _ in range(3):
-                z.gather(t, idx_dev, out, stream=stream)
+                z.gather_variant(t, idx_dev, out, args.variant, stream=stream)
             torch.cuda.synchronize()
             ms = []
             for _ in range(max(5, min(args.steps, 20))):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
-                z.gather(t, idx_dev, out, stream=stream)
+                z.gather_variant(t, idx_dev, out, args.variant, stream=stream)
                 e1.record(stream)
                 e1.synchronize()
                 ms.append(e0.elapsed_time(e1))
@@ -420,7 +420,8 @@ def main():
                     help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep; "
                          "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning; 8 = producer/consumer pipeline")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
-    ap.add_argument("--variant", type=int, default=0, help="force a kernel (ablation)")
+    ap.add_argument("--variant", type=int, default=0,
+                    help="force a kernel (ablation; configs 1-5): 1 naive, 2 rowvec, 3 aligned, 4 halfline")
     ap.add_argument("--sorted", action="store_true", help="ascending index lists (secondary order)")
     ap.add_argument("--max-table-gb", type=float, default=200.0)
     ap.add_argument("--no-baselines", action="store_true", help="skip the CPU legs (for profiling)")
