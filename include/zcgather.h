@@ -162,7 +162,9 @@ int zcg_unregister_table(zcg_table* t);
  * synchronisation, no host read of idx_dev.
  *   idx_dev : device, n_idx int64, each in [0, n_rows). Out-of-range entries
  *             are NOT checked here (undefined behaviour, as in the paper's
- *             kernel); use zcg_validate_indices when in doubt.
+ *             kernel); use zcg_validate_indices when in doubt. Any address the
+ *             GPU can read will do, mapped pinned host memory included (the
+ *             list is then fetched over the link too, 8 bytes per row).
  *   out_dev : device, CALLER-OWNED, n_idx*row_bytes bytes, aligned to the
  *             element size (16-byte alignment enables the widest accesses),
  *             must not overlap the table (ZCG_EALIAS).
@@ -171,6 +173,9 @@ int zcg_unregister_table(zcg_table* t);
  * change while a gather that reads it runs; rows the host rewrites after a
  * gather has completed are seen by every later gather (the GPU's caches, the
  * scalar cache included, are invalidated when a kernel starts).
+ * Safe under stream capture (one kernel node, nothing else is recorded): a
+ * replayed graph reads whatever idx_dev and the table hold at replay time.
+ * Calls on one handle may come from any number of host threads and streams.
  */
 int zcg_gather(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
                void* stream);
@@ -205,6 +210,8 @@ int zcg_gather_ordered(const zcg_table* t, const int64_t* idx_dev, const int64_t
  * zcg_order_workspace_bytes(n_idx) bytes, free to reuse once the stream has
  * passed the call). n_rows bounds the index values (only the bits below it are
  * sorted). Equal indices keep their list order.
+ * Not meant for stream capture: the library sort may record memory-set
+ * operations of its own. Build the order eagerly, capture zcg_gather_ordered.
  */
 int zcg_order_workspace_bytes(int64_t n_idx, int64_t* bytes);
 int zcg_make_order(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_t* order_dev,
