@@ -388,9 +388,120 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
             cs.close()
         return ms
 
+    # The same with the sampler inside the loop (Section 3.3: sampling, gathering and training are
+    # three stages; the first two run beside the third). Lists are drawn live from the graph.
+    def sampler_graph():
+        return wl.PowerLawGraph(table.n_rows, cfg.graph[0], cfg.graph[1], cfg.seed)
+
+    bound_rows = cfg.n_seeds
+    for f in cfg.fanout:
+        bound_rows *= f + 1
+
+    def serial_with_sampler():
+        g = sampler_graph()
+        big = torch.empty((bound_rows, cfg.dim), dtype=torch.float32, device="cuda")
+        idx_big = torch.empty(bound_rows, dtype=torch.int64, device="cuda")
+        t_s = 0.0
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for b in range(reps):
+            ts = time.perf_counter()
+            a = torch.from_numpy(g.sample_minibatch(cfg.n_seeds, cfg.fanout, b)[0])
+            t_s += time.perf_counter() - ts
+            idx_big[:a.numel()].copy_(a, non_blocking=False)
+            z.gather(table, idx_big, big, n_idx=a.numel(), stream=cur)
+            z.synthetic_compute(cur, comp_blocks, iters, sink)
+            torch.cuda.synchronize()
+        ms = (time.perf_counter() - t) / reps * 1e3
+        g.close()
+        return ms, t_s / reps * 1e3
+
+    def threaded(gather_cus, n_samplers=1):
+        import queue
+        import threading
+        g = sampler_graph()
+        lists_q = queue.Queue(maxsize=2 * n_samplers)
+        counter, counter_lock = [0], threading.Lock()
+
+        def sampler():  # several samplers feed one producer, as the paper's sampler workers do
+            mine = sampler_graph()  # a graph object carries its own visited-bitmap: one per thread
+            try:
+                while True:
+                    with counter_lock:
+                        b = counter[0]
+                        counter[0] += 1
+                    if b >= reps:
+                        return
+                    lists_q.put(mine.sample_minibatch(cfg.n_seeds, cfg.fanout, b)[0])
+            finally:
+                mine.close()
+        tbufs = [torch.empty((bound_rows, cfg.dim), dtype=torch.float32, device="cuda") for _ in range(2)]
+        if gather_cus:
+            gs = z.stream_create_cu_mask(list(range(gather_cus)))
+            cs = z.stream_create_cu_mask(list(range(gather_cus, n_cus)))
+            cons = torch.cuda.ExternalStream(cs.cuda_stream)
+        else:
+            gs, cs, cons = None, None, torch.cuda.Stream()
+        pipe = z.pipeline_create(table, bound_rows, tbufs, gs)
+        failed = []
+
+        def producer():
+            try:
+                torch.cuda.set_device(0)
+                for b in range(reps):
+                    a = (lists_q.get(timeout=60) if n_samplers > 1
+                         else g.sample_minibatch(cfg.n_seeds, cfg.fanout, b)[0])
+                    pipe.submit(a, timeout_ms=60_000)
+            except Exception as exc:  # noqa: BLE001
+                failed.append(repr(exc))
+            finally:
+                pipe.finish()
+
+        def consumer():
+            try:
+                torch.cuda.set_device(0)
+                while True:
+                    slot = pipe.next(timeout_ms=60_000)
+                    if slot is None:
+                        break
+                    pipe.acquire(slot, cons)
+                    z.synthetic_compute(cons, comp_blocks, iters, sink)
+                    pipe.release(slot, cons)
+                cons.synchronize()
+            except Exception as exc:  # noqa: BLE001
+                failed.append(repr(exc))
+
+        tp, tc = threading.Thread(target=producer), threading.Thread(target=consumer)
+        samplers = [threading.Thread(target=sampler) for _ in range(n_samplers if n_samplers > 1 else 0)]
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for th in samplers + [tc, tp]:
+            th.start()
+        for th in samplers + [tp, tc]:
+            th.join()
+        ms = (time.perf_counter() - t) / reps * 1e3
+        pipe.close()
+        if gs:
+            gs.close()
+            cs.close()
+        g.close()
+        if failed:
+            raise RuntimeError(f"threaded pipeline failed: {failed}")
+        return ms
+
     cases = []
     if serial_ms is not None:
         cases.append({"mode": "one stream, step by step", "ms_per_minibatch": round(serial_ms, 3)})
+    if only in ("all", "threads"):
+        ms, sample_ms = serial_with_sampler()
+        cases.append({"mode": "sampler in the loop, one stream, step by step", "ms_per_minibatch": round(ms, 3),
+                      "sampler_ms": round(sample_ms, 3)})
+        cases.append({"mode": "sampler+producer thread | consumer thread, 2 buffers, no masks",
+                      "ms_per_minibatch": round(threaded(0), 3)})
+        cases.append({"mode": f"sampler+producer thread | consumer thread, 2 buffers, gather on 16 CUs / compute on {n_cus - 16}",
+                      "ms_per_minibatch": round(threaded(16), 3)})
+        cases.append({"mode": f"4 sampler threads -> producer thread | consumer thread, 2 buffers, gather on 16 CUs / compute on {n_cus - 16}",
+                      "ms_per_minibatch": round(threaded(16, 4), 3)})
     if only in ("all", "nomask"):
         cases.append({"mode": "pipeline, 2 buffers, no masks", "ms_per_minibatch": round(pipelined(0), 3)})
     for n in (8, 16, 24):
@@ -426,7 +537,7 @@ def main():
     ap.add_argument("--max-table-gb", type=float, default=200.0)
     ap.add_argument("--no-baselines", action="store_true", help="skip the CPU legs (for profiling)")
     ap.add_argument("--pipeline-mode", default="all",
-                    choices=["all", "serial", "nomask", "mask8", "mask16", "mask24"],
+                    choices=["all", "serial", "nomask", "mask8", "mask16", "mask24", "threads"],
                     help="config 8: run one mode only (for kernel-trace profiles)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy, as the known-size reference for counters")

@@ -39,6 +39,8 @@ extern "C" {
 #define ZCG_EALIAS (-7)  /* output range overlaps the table                     */
 #define ZCG_ERANGE (-8)  /* an index is outside [0, n_rows) (host-side checks)  */
 #define ZCG_EBUSY (-9)   /* pipeline: the next buffer has not been released yet */
+#define ZCG_ETIMEDOUT (-10) /* pipeline: a bounded wait ran out                   */
+#define ZCG_ECLOSED (-11)   /* pipeline: the producer has finished                */
 
 /* ---- element types: only the size matters, payload bits are never read -- */
 #define ZCG_F16 1 /* 2-byte elements (fp16, bf16, int16)         */
@@ -297,8 +299,10 @@ int zcg_synthetic_compute(void* stream, int blocks, int64_t iters, float* sink_d
  *   gather_stream : stream the list copies and gathers run on (e.g. one from
  *                   zcg_stream_create_cu_mask); NULL = the pipeline creates its own
  * The pipeline owns, per buffer, a pinned staging area and a device copy of the
- * index list (max_rows int64 each). Not thread-safe: one producer thread calls
- * submit, and acquire/release for a slot follow its submit.
+ * index list (max_rows int64 each). Threads: ONE producer thread (submit,
+ * submit_wait, finish) and ONE consumer thread (next, acquire, release) may run
+ * at the same time; they may also be the same thread. The consumer takes slot
+ * numbers either from submit's result or from zcg_pipeline_next, not from both.
  */
 typedef struct zcg_pipeline zcg_pipeline;
 int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, void* const* out_bufs,
@@ -311,12 +315,30 @@ int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, voi
  * released that buffer since its last use (nothing is enqueued then).
  */
 int zcg_pipeline_submit(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx, int* slot);
-/* Consumer: make consumer_stream wait for that gather; yields the buffer and its row count. */
+/*
+ * Same, but a producer thread sleeps until the consumer thread releases the buffer:
+ * timeout_ms < 0 waits without limit, otherwise ZCG_ETIMEDOUT after that long
+ * (0 behaves like zcg_pipeline_submit). This is the back-pressure of the paper's
+ * bounded queue between producer and consumer.
+ */
+int zcg_pipeline_submit_wait(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx,
+                             int timeout_ms, int* slot);
+/* Producer: no further minibatch will come; wakes a consumer blocked in next. */
+int zcg_pipeline_finish(zcg_pipeline* p);
+/*
+ * Consumer: the next submitted minibatch, in submission order. Sleeps until one is
+ * there (timeout_ms as above: ZCG_ETIMEDOUT); ZCG_ECLOSED once the producer has
+ * finished and every minibatch has been handed out. Follow with acquire / release.
+ */
+int zcg_pipeline_next(zcg_pipeline* p, int timeout_ms, int* slot);
+/* Consumer: make consumer_stream wait for that gather; yields the buffer and its row count.
+ * ZCG_EINVAL for a slot that holds no submitted, unreleased minibatch. */
 int zcg_pipeline_acquire(zcg_pipeline* p, int slot, void* consumer_stream, void** out_dev,
                          int64_t* n_rows);
 /* Consumer: work enqueued so far on consumer_stream is the last that reads the buffer. */
 int zcg_pipeline_release(zcg_pipeline* p, int slot, void* consumer_stream);
-/* Waits for the gather stream, frees what the pipeline owns (never the output buffers). */
+/* Waits for the gather stream, frees what the pipeline owns (never the output buffers).
+ * No other thread may still be inside a call on p. */
 int zcg_pipeline_destroy(zcg_pipeline* p);
 
 /*

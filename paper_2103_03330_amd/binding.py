@@ -19,8 +19,8 @@ import numpy as np
 from . import build as _build
 
 # status codes / constants (include/zcgather.h)
-OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE, EBUSY = (
-    0, -1, -2, -3, -4, -5, -6, -7, -8, -9)
+OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE, EBUSY, ETIMEDOUT, ECLOSED = (
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11)
 F16, F32, B8, B64 = 1, 2, 3, 4
 ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER, ALLOC_UNCACHED = 0, 1, 2, 4
 VARIANT_AUTO, VARIANT_NAIVE, VARIANT_ROWVEC, VARIANT_ALIGNED, VARIANT_HALFLINE = 0, 1, 2, 3, 4
@@ -37,7 +37,8 @@ EXPORTS = [
     "zcg_gather_ex", "zcg_plan_gather", "zcg_validate_indices", "zcg_cpu_gather_memcpy",
     "zcg_cpu_gather_memcpy_chunked", "zcg_measure_h2d", "zcg_pinned_alloc", "zcg_pinned_free",
     "zcg_version", "zcg_stream_create_cu_mask", "zcg_stream_destroy", "zcg_device_cu_count",
-    "zcg_synthetic_compute", "zcg_pipeline_create", "zcg_pipeline_submit", "zcg_pipeline_acquire",
+    "zcg_synthetic_compute", "zcg_pipeline_create", "zcg_pipeline_submit", "zcg_pipeline_submit_wait",
+    "zcg_pipeline_finish", "zcg_pipeline_next", "zcg_pipeline_acquire",
     "zcg_pipeline_release", "zcg_pipeline_destroy", "zcg_gather_ordered",
     "zcg_order_workspace_bytes", "zcg_make_order", "zcg_measure_host_read_latency",
 ]
@@ -113,6 +114,9 @@ def load_library() -> ctypes.CDLL:
         "zcg_synthetic_compute": (i32, [vp, i32, i64, vp]),
         "zcg_pipeline_create": (i32, [vp, i64, i32, ctypes.POINTER(ctypes.c_void_p), vp, pvp]),
         "zcg_pipeline_submit": (i32, [vp, vp, i64, ctypes.POINTER(i32)]),
+        "zcg_pipeline_submit_wait": (i32, [vp, vp, i64, i32, ctypes.POINTER(i32)]),
+        "zcg_pipeline_finish": (i32, [vp]),
+        "zcg_pipeline_next": (i32, [vp, i32, ctypes.POINTER(i32)]),
         "zcg_pipeline_acquire": (i32, [vp, i32, vp, pvp, ctypes.POINTER(i64)]),
         "zcg_pipeline_release": (i32, [vp, i32, vp]),
         "zcg_pipeline_destroy": (i32, [vp]),
@@ -393,11 +397,32 @@ class Pipeline:
                "zcg_pipeline_create")
         self.handle = int(out.value)
 
-    def submit(self, idx_host) -> int:
+    def submit(self, idx_host, timeout_ms: Optional[int] = None) -> int:
+        """Enqueue one minibatch; returns its slot. Without ``timeout_ms`` a ring that is full
+        raises EBUSY at once; with it (negative = no limit) the call sleeps until the consumer
+        thread releases the buffer."""
         a = _host_idx(idx_host)
         slot = ctypes.c_int(-1)
-        _check(load_library().zcg_pipeline_submit(self.handle, a.ctypes.data, a.size,
-                                                  ctypes.byref(slot)), "zcg_pipeline_submit")
+        if timeout_ms is None:
+            _check(load_library().zcg_pipeline_submit(self.handle, a.ctypes.data, a.size,
+                                                      ctypes.byref(slot)), "zcg_pipeline_submit")
+        else:
+            _check(load_library().zcg_pipeline_submit_wait(self.handle, a.ctypes.data, a.size,
+                                                           int(timeout_ms), ctypes.byref(slot)),
+                   "zcg_pipeline_submit_wait")
+        return int(slot.value)
+
+    def finish(self) -> None:
+        _check(load_library().zcg_pipeline_finish(self.handle), "zcg_pipeline_finish")
+
+    def next(self, timeout_ms: int = -1) -> Optional[int]:
+        """Consumer: slot of the next submitted minibatch, None once the producer has finished
+        and the ring is drained."""
+        slot = ctypes.c_int(-1)
+        rc = load_library().zcg_pipeline_next(self.handle, int(timeout_ms), ctypes.byref(slot))
+        if rc == ECLOSED:
+            return None
+        _check(rc, "zcg_pipeline_next")
         return int(slot.value)
 
     def acquire(self, slot: int, consumer_stream=None):

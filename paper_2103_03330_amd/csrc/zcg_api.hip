@@ -91,6 +91,8 @@ const char* zcg_strerror(int status) {
     case ZCG_EALIAS: return "output overlaps the table";
     case ZCG_ERANGE: return "index out of range";
     case ZCG_EBUSY: return "buffer not released by the consumer";
+    case ZCG_ETIMEDOUT: return "wait timed out";
+    case ZCG_ECLOSED: return "pipeline finished by the producer";
     default: return "unknown status";
   }
 }

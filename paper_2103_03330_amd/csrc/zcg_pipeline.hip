@@ -4,10 +4,16 @@
 // reads that buffer in place. Buffers alternate (ping-pong), and producer and
 // consumer meet once per minibatch -- here through HIP events between a gather
 // stream owned by the pipeline and the caller's consumer stream, inside one
-// process, instead of IPC handles between processes.
+// process, instead of IPC handles between processes. The paper's queue between
+// the producer and the consumer process is the ring itself: a mutex and a
+// condition variable let one producer thread and one consumer thread block on
+// "a buffer is free" and "a minibatch is ready".
 #include <hip/hip_runtime.h>
 
+#include <chrono>
+#include <condition_variable>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -17,19 +23,31 @@ struct zcg_pipeline {
   const zcg_table* table = nullptr;
   int64_t max_rows = 0;
   int n_buffers = 0;
-  int next = 0;
   bool own_stream = false;
   hipStream_t gather_stream = nullptr;
+  // A buffer goes FREE -> FILLING (producer is enqueuing into it) -> READY (its
+  // gather is enqueued and `gathered` recorded) -> FREE again on release.
+  enum State { FREE, FILLING, READY };
   struct Slot {
     void* out = nullptr;            // caller-owned
     int64_t* idx_dev = nullptr;     // library-owned
     int64_t* idx_pinned = nullptr;  // library-owned
     hipEvent_t gathered = nullptr;  // recorded on the gather stream after the gather
     hipEvent_t released = nullptr;  // recorded on the consumer stream by release()
-    bool used = false, has_release = false;
+    State state = FREE;
+    bool ever_used = false;    // `gathered` has been recorded at least once
+    bool has_release = false;  // `released` was recorded since the last use
+    bool delivered = false;    // handed to the consumer by zcg_pipeline_next
     int64_t n_rows = 0;
   };
   std::vector<Slot> slots;
+  // guarded by mu
+  std::mutex mu;
+  std::condition_variable cv;
+  int next_fill = 0;     // buffer the next submit uses
+  int next_deliver = 0;  // buffer the next zcg_pipeline_next hands out
+  int ready_undelivered = 0;
+  bool finished = false;
 };
 
 namespace {
@@ -42,6 +60,88 @@ void free_slots(zcg_pipeline* p) {
     if (s.idx_pinned) (void)hipHostFree(s.idx_pinned);
   }
   if (p->own_stream && p->gather_stream) (void)hipStreamDestroy(p->gather_stream);
+}
+
+struct DeviceScope {
+  int prev = -1;
+  hipError_t err;
+  explicit DeviceScope(int device) {
+    err = hipGetDevice(&prev);
+    if (err == hipSuccess && prev != device) err = hipSetDevice(device);
+  }
+  ~DeviceScope() {
+    int cur = -1;
+    if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+  }
+};
+
+// Waits on cv until pred() holds; timeout_ms < 0 waits without limit, 0 only tests.
+template <class Pred>
+bool wait_for(zcg_pipeline* p, std::unique_lock<std::mutex>& lk, int timeout_ms, Pred pred) {
+  if (timeout_ms < 0) {
+    p->cv.wait(lk, pred);
+    return true;
+  }
+  return p->cv.wait_for(lk, std::chrono::milliseconds(timeout_ms), pred);
+}
+
+int submit_impl(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx, int timeout_ms, int* slot) {
+  if (!p || !slot || n_idx < 0 || n_idx > p->max_rows || (n_idx > 0 && !idx_host)) return ZCG_EINVAL;
+  if (!zcg_is_live(p->table)) return ZCG_EHANDLE;
+  for (int64_t i = 0; i < n_idx; ++i)
+    if (idx_host[i] < 0 || idx_host[i] >= p->table->n_rows) return ZCG_ERANGE;
+  int k;
+  bool wait_copy, wait_release;
+  {
+    std::unique_lock<std::mutex> lk(p->mu);
+    if (p->finished) return ZCG_ECLOSED;
+    k = p->next_fill;
+    auto& s = p->slots[(size_t)k];
+    if (s.state == zcg_pipeline::FILLING) return ZCG_EINVAL;  // a second producer thread
+    // the consumer still holds this buffer: nothing is enqueued until it lets go
+    if (!wait_for(p, lk, timeout_ms, [&] { return s.state == zcg_pipeline::FREE; }))
+      return timeout_ms == 0 ? ZCG_EBUSY : ZCG_ETIMEDOUT;
+    s.state = zcg_pipeline::FILLING;
+    wait_copy = s.ever_used;
+    wait_release = s.has_release;
+  }
+  auto& s = p->slots[(size_t)k];  // FILLING: only this thread touches the slot now
+  DeviceScope scope(p->table->device);
+  hipError_t e = scope.err;
+  // the previous list copy out of this slot's staging memory must be over (it is, unless the
+  // producer runs a whole ring ahead of the GPU): a host-side wait, taken outside the lock
+  if (e == hipSuccess && wait_copy) e = hipEventSynchronize(s.gathered);
+  // the consumer's last reads of this buffer: a device-side wait, the host does not block
+  if (e == hipSuccess && wait_release) e = hipStreamWaitEvent(p->gather_stream, s.released, 0);
+  int rc = ZCG_OK;
+  if (e == hipSuccess && n_idx > 0) {
+    std::memcpy(s.idx_pinned, idx_host, (size_t)n_idx * sizeof(int64_t));
+    e = hipMemcpyAsync(s.idx_dev, s.idx_pinned, (size_t)n_idx * sizeof(int64_t),
+                       hipMemcpyHostToDevice, p->gather_stream);
+    if (e == hipSuccess) rc = zcg_gather(p->table, s.idx_dev, n_idx, s.out, p->gather_stream);
+  }
+  // recorded even after a failure above when possible: whatever did get enqueued must be
+  // covered by the event the next use of this slot waits for
+  hipError_t e2 = hipEventRecord(s.gathered, p->gather_stream);
+  if (e == hipSuccess) e = e2;
+  {
+    std::lock_guard<std::mutex> lk(p->mu);
+    if (e2 == hipSuccess) s.ever_used = true;
+    if (e != hipSuccess || rc != ZCG_OK) {
+      s.state = zcg_pipeline::FREE;  // has_release stays: the consumer's event still stands
+      p->cv.notify_all();
+      return e != hipSuccess ? zcg_fail_hip(e) : rc;
+    }
+    s.has_release = false;
+    s.delivered = false;
+    s.n_rows = n_idx;
+    s.state = zcg_pipeline::READY;
+    p->next_fill = (k + 1) % p->n_buffers;
+    ++p->ready_undelivered;
+    *slot = k;
+  }
+  p->cv.notify_all();
+  return ZCG_OK;
 }
 
 }  // namespace
@@ -58,6 +158,8 @@ int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, voi
     if (!out_bufs[i]) return ZCG_EINVAL;
     if ((uintptr_t)out_bufs[i] % (uintptr_t)t->elem) return ZCG_EALIGN;
   }
+  DeviceScope scope(t->device);
+  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
   zcg_pipeline* p = new (std::nothrow) zcg_pipeline;
   if (!p) return ZCG_ENOMEM;
   p->table = t;
@@ -91,42 +193,47 @@ int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, voi
 }
 
 int zcg_pipeline_submit(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx, int* slot) {
-  if (!p || !slot || n_idx < 0 || n_idx > p->max_rows || (n_idx > 0 && !idx_host)) return ZCG_EINVAL;
-  if (!zcg_is_live(p->table)) return ZCG_EHANDLE;
-  for (int64_t i = 0; i < n_idx; ++i)
-    if (idx_host[i] < 0 || idx_host[i] >= p->table->n_rows) return ZCG_ERANGE;
-  const int k = p->next;
-  auto& s = p->slots[(size_t)k];
-  if (s.used && !s.has_release) return ZCG_EBUSY;  // the consumer still holds this buffer
-  hipError_t e = hipSuccess;
-  // the previous list copy out of this slot's staging memory must be over (it is, unless the
-  // producer runs a whole ring ahead): the only host-side wait, and it is the back-pressure
-  if (s.used) e = hipEventSynchronize(s.gathered);
-  // the consumer must be done with this buffer: a device-side wait, the host does not block
-  if (e == hipSuccess && s.has_release) e = hipStreamWaitEvent(p->gather_stream, s.released, 0);
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  if (n_idx > 0) {
-    std::memcpy(s.idx_pinned, idx_host, (size_t)n_idx * sizeof(int64_t));
-    e = hipMemcpyAsync(s.idx_dev, s.idx_pinned, (size_t)n_idx * sizeof(int64_t),
-                       hipMemcpyHostToDevice, p->gather_stream);
-    if (e != hipSuccess) return zcg_fail_hip(e);
-    int rc = zcg_gather(p->table, s.idx_dev, n_idx, s.out, p->gather_stream);
-    if (rc) return rc;
+  return submit_impl(p, idx_host, n_idx, 0, slot);
+}
+
+int zcg_pipeline_submit_wait(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx,
+                             int timeout_ms, int* slot) {
+  return submit_impl(p, idx_host, n_idx, timeout_ms, slot);
+}
+
+int zcg_pipeline_finish(zcg_pipeline* p) {
+  if (!p) return ZCG_EINVAL;
+  {
+    std::lock_guard<std::mutex> lk(p->mu);
+    p->finished = true;
   }
-  e = hipEventRecord(s.gathered, p->gather_stream);
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  s.used = true;
-  s.has_release = false;
-  s.n_rows = n_idx;
-  *slot = k;
-  p->next = (k + 1) % p->n_buffers;
+  p->cv.notify_all();
   return ZCG_OK;
+}
+
+int zcg_pipeline_next(zcg_pipeline* p, int timeout_ms, int* slot) {
+  if (!p || !slot) return ZCG_EINVAL;
+  std::unique_lock<std::mutex> lk(p->mu);
+  const bool ok =
+      wait_for(p, lk, timeout_ms, [&] { return p->ready_undelivered > 0 || p->finished; });
+  if (p->ready_undelivered > 0) {
+    *slot = p->next_deliver;
+    p->slots[(size_t)*slot].delivered = true;
+    p->next_deliver = (p->next_deliver + 1) % p->n_buffers;
+    --p->ready_undelivered;
+    return ZCG_OK;
+  }
+  if (p->finished) return ZCG_ECLOSED;
+  (void)ok;
+  return ZCG_ETIMEDOUT;
 }
 
 int zcg_pipeline_acquire(zcg_pipeline* p, int slot, void* consumer_stream, void** out_dev,
                          int64_t* n_rows) {
-  if (!p || slot < 0 || slot >= p->n_buffers || !p->slots[(size_t)slot].used) return ZCG_EINVAL;
+  if (!p || slot < 0 || slot >= p->n_buffers) return ZCG_EINVAL;
+  std::lock_guard<std::mutex> lk(p->mu);
   auto& s = p->slots[(size_t)slot];
+  if (s.state != zcg_pipeline::READY) return ZCG_EINVAL;
   hipError_t e = hipStreamWaitEvent(static_cast<hipStream_t>(consumer_stream), s.gathered, 0);
   if (e != hipSuccess) return zcg_fail_hip(e);
   if (out_dev) *out_dev = s.out;
@@ -135,11 +242,21 @@ int zcg_pipeline_acquire(zcg_pipeline* p, int slot, void* consumer_stream, void*
 }
 
 int zcg_pipeline_release(zcg_pipeline* p, int slot, void* consumer_stream) {
-  if (!p || slot < 0 || slot >= p->n_buffers || !p->slots[(size_t)slot].used) return ZCG_EINVAL;
-  auto& s = p->slots[(size_t)slot];
-  hipError_t e = hipEventRecord(s.released, static_cast<hipStream_t>(consumer_stream));
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  s.has_release = true;
+  if (!p || slot < 0 || slot >= p->n_buffers) return ZCG_EINVAL;
+  {
+    std::lock_guard<std::mutex> lk(p->mu);
+    auto& s = p->slots[(size_t)slot];
+    if (s.state != zcg_pipeline::READY) return ZCG_EINVAL;
+    hipError_t e = hipEventRecord(s.released, static_cast<hipStream_t>(consumer_stream));
+    if (e != hipSuccess) return zcg_fail_hip(e);
+    s.has_release = true;
+    s.state = zcg_pipeline::FREE;
+    if (!s.delivered) {  // the consumer works from submit's slot numbers, not from next()
+      --p->ready_undelivered;
+      p->next_deliver = (slot + 1) % p->n_buffers;
+    }
+  }
+  p->cv.notify_all();
   return ZCG_OK;
 }
 

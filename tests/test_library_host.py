@@ -25,7 +25,7 @@ def test_header_and_library_agree_on_exports():
 
 
 def test_status_strings():
-    for code in range(0, -10, -1):
+    for code in range(0, -12, -1):
         assert z.strerror(code) != "unknown status"
     assert z.strerror(-99) == "unknown status"
 
@@ -247,3 +247,14 @@ def test_handle_registry_is_thread_safe():
     for th in threads:
         th.join()
     assert not errors, errors[:3]
+
+
+def test_pipeline_calls_reject_null_without_touching_the_gpu():
+    import ctypes
+    lib = z.load_library()
+    slot = ctypes.c_int(-1)
+    assert lib.zcg_pipeline_next(None, 0, ctypes.byref(slot)) == z.binding.EINVAL
+    assert lib.zcg_pipeline_finish(None) == z.binding.EINVAL
+    assert lib.zcg_pipeline_submit_wait(None, None, 0, 0, ctypes.byref(slot)) == z.binding.EINVAL
+    assert lib.zcg_pipeline_release(None, 0, None) == z.binding.EINVAL
+    assert lib.zcg_pipeline_destroy(None) == z.binding.EINVAL

@@ -71,3 +71,110 @@ def test_ring_delivers_every_minibatch(n_buffers, masked, slow_consumer):
         if gstream:
             gstream.close()
         table.close()
+
+
+def test_producer_thread_and_consumer_thread():
+    """The paper's arrangement: a producer (sampler + gather) and a consumer run side by side and
+    meet through a bounded queue. Here they are two host threads on the ring's blocking calls."""
+    import threading
+
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    torch.cuda.set_device(0)
+    n_rows, dim, n_batches, n_buffers = 80_000, 100, 30, 2
+    table = z.alloc_table(n_rows, dim, "f32")
+    wl.fill_table_ptr(table.host_ptr, n_rows, dim, "f32", seed=41)
+    g = wl.PowerLawGraph(n_rows, 25.0, 2.1, seed=9)
+    max_rows = 128 * 11 * 6
+    bufs = [torch.zeros((max_rows, dim), dtype=torch.float32, device="cuda") for _ in range(n_buffers)]
+    pipe = z.pipeline_create(table, max_rows, bufs)
+    submitted, results, errors = [], [], []
+
+    def producer():
+        try:
+            torch.cuda.set_device(0)
+            for b in range(n_batches):
+                idx = g.sample_minibatch(128, (10, 5), b)[0]
+                submitted.append(idx)
+                pipe.submit(idx, timeout_ms=20_000)
+            pipe.finish()
+        except Exception as exc:  # noqa: BLE001
+            errors.append(("producer", repr(exc)))
+            pipe.finish()
+
+    def consumer():
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+            while True:
+                slot = pipe.next(timeout_ms=20_000)
+                if slot is None:
+                    break
+                buf, n = pipe.acquire(slot, stream)
+                with torch.cuda.stream(stream):
+                    z.synthetic_compute(stream, 512, 4000, sink)  # the consumer is the slower side
+                    results.append(buf[:n].clone())
+                pipe.release(slot, stream)
+            stream.synchronize()
+        except Exception as exc:  # noqa: BLE001
+            errors.append(("consumer", repr(exc)))
+
+    tp, tc = threading.Thread(target=producer), threading.Thread(target=consumer)
+    try:
+        tc.start()
+        tp.start()
+        tp.join(timeout=100)
+        tc.join(timeout=100)
+        assert not tp.is_alive() and not tc.is_alive()
+        assert not errors, errors
+        assert len(results) == n_batches == len(submitted)
+        host = table.host_array()
+        for b, (idx, got) in enumerate(zip(submitted, results)):
+            assert got.cpu().numpy().tobytes() == oracle_gather(host, idx).tobytes(), f"minibatch {b}"
+        # after finish: the producer is refused, the consumer is told the stream has ended
+        with pytest.raises(z.ZcgError) as e:
+            pipe.submit(submitted[0])
+        assert e.value.status == z.ECLOSED
+        assert pipe.next(timeout_ms=0) is None
+    finally:
+        torch.cuda.synchronize()
+        pipe.close()
+        g.close()
+        table.close()
+
+
+def test_bounded_waits_time_out():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    torch.cuda.set_device(0)
+    n_rows, dim = 10_000, 64
+    table = z.alloc_table(n_rows, dim, "f16")
+    wl.fill_table_ptr(table.host_ptr, n_rows, dim, "f16", seed=43)
+    bufs = [torch.zeros((100, dim), dtype=torch.float16, device="cuda")]
+    pipe = z.pipeline_create(table, 100, bufs)
+    try:
+        with pytest.raises(z.ZcgError) as e:
+            pipe.next(timeout_ms=30)  # nothing submitted
+        assert e.value.status == z.ETIMEDOUT
+        idx = np.arange(100, dtype=np.int64)
+        slot = pipe.submit(idx)
+        with pytest.raises(z.ZcgError) as e:
+            pipe.submit(idx, timeout_ms=30)  # the only buffer is held
+        assert e.value.status == z.ETIMEDOUT
+        with pytest.raises(z.ZcgError) as e:
+            pipe.submit(idx)
+        assert e.value.status == z.EBUSY
+        assert pipe.next(timeout_ms=0) == slot
+        buf, n = pipe.acquire(slot)
+        torch.cuda.synchronize()
+        assert n == 100 and buf[:n].cpu().numpy().tobytes() == oracle_gather(table.host_array(), idx).tobytes()
+        pipe.release(slot)
+        with pytest.raises(z.ZcgError) as e:
+            pipe.release(slot)  # already released
+        assert e.value.status == z.binding.EINVAL
+        assert pipe.submit(idx, timeout_ms=30) == 0
+    finally:
+        torch.cuda.synchronize()
+        pipe.close()
+        table.close()
