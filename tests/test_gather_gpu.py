@@ -392,3 +392,29 @@ def test_host_updates_between_gathers_are_seen(flags):
                 host[:] = host[::-1].copy() if round_ % 2 == 0 else host * np.float32(0.5)
     finally:
         table.close()
+
+
+@pytest.mark.parametrize("n_rows,dim,dtype", [(40, 70_001, "f32"), (24, 65_536, "f16"), (16, 300_003, "i8"),
+                                               (12, 40_000, "f64")])
+def test_very_wide_rows_and_first_last_row(n_rows, dim, dtype):
+    """Rows of hundreds of KB (many passes per wave) and lists that name only the first and
+    the last row of the table, for every kernel; also ordered."""
+    table = host_table(n_rows, dim, dtype, seed=dim)
+    try:
+        host = table.host_array()
+        lists = [np.array([n_rows - 1], np.int64), np.array([0], np.int64),
+                 np.array([n_rows - 1, 0, n_rows - 1, 0, 1], np.int64),
+                 wl.uniform_indices(67, n_rows, seed=3)]
+        for idx in lists:
+            want = oracle_gather(host, idx)
+            for variant in ALL_VARIANTS:
+                got = run_gather(table, idx, dtype, z.LaunchOpts(variant=variant))
+                assert_same_bits(got, want, f"{dtype} dim={dim} n_idx={len(idx)} variant={variant}")
+            idx_dev = torch.from_numpy(idx).cuda()
+            order = torch.from_numpy(np.argsort(idx, kind="stable")).cuda()
+            out = torch.zeros((len(idx), dim), dtype=TORCH_DT[dtype], device="cuda")
+            z.gather_ordered(table, idx_dev, order, out)
+            torch.cuda.synchronize()
+            assert_same_bits(out, want, f"ordered {dtype} dim={dim} n_idx={len(idx)}")
+    finally:
+        table.close()
