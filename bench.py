@@ -522,6 +522,50 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
             "cases": cases}
 
 
+def run_list_length(args, z, wl, np, torch, link_peak):
+    """Gather time against list length for rows of 512 B ... 1 MiB: where the launch and the first
+    round trip dominate, where the link fills, and what giving several wavefronts to one long
+    row (row_splits) is worth on short lists of long rows."""
+    cur = torch.cuda.current_stream()
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(max(10, min(args.steps, 30))):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(cur)
+            fn()
+            e1.record(cur)
+            e1.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return float(np.median(ms))
+
+    pts = []
+    for dim, n_rows in ((128, 2_000_000), (1024, 500_000), (16_384, 40_000), (262_144, 2_000)):
+        table = z.alloc_table(n_rows, dim, "f32")
+        wl.fill_table_ptr(table.host_ptr, n_rows, dim, "f32", seed=wl.MASTER_SEED + 9)
+        rb = dim * 4
+        for n_idx in (1, 4, 16, 64, 256, 1024, 4096, 16384, 65536):
+            if n_idx * rb > 1.2e9:
+                break
+            idx = torch.from_numpy(wl.uniform_indices(n_idx, n_rows, seed=n_idx)).cuda()
+            out = torch.empty((n_idx, dim), dtype=torch.float32, device="cuda")
+            plan = z.plan_gather(table, n_idx, out)
+            us = timed(lambda: z.gather(table, idx, out, stream=cur)) * 1e3
+            pt = {"row_bytes": rb, "n_idx": n_idx, "us": round(us, 1),
+                  "gbps": round(n_idx * rb / us / 1e3, 2), "row_splits": plan["row_splits"]}
+            if plan["row_splits"] > 1:
+                one = z.LaunchOpts(row_splits=1)
+                us1 = timed(lambda: z.gather_ex(table, idx, out, one, stream=cur)) * 1e3
+                pt["us_one_wavefront_per_row"] = round(us1, 1)
+            pts.append(pt)
+            print(f"# {pt}", file=sys.stderr, flush=True)
+        table.close()
+    return pts
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -529,7 +573,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep; "
-                         "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning; 8 = producer/consumer pipeline")
+                         "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning; "
+                         "8 = producer/consumer pipeline; 9 = list-length sweep")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
     ap.add_argument("--variant", type=int, default=0,
                     help="force a kernel (ablation; configs 1-5): 1 naive, 2 rowvec, 3 aligned, 4 halfline")
@@ -573,6 +618,14 @@ def main():
                           "sweep": pts}))
         return
 
+    if args.config == 9:
+        pts = run_list_length(args, z, wl, np, torch, link_peak)
+        print(json.dumps({"metric": METRIC, "unit": "GB/s", "n_gpus": 1, "data": "synthetic",
+                          "config": {"workload": "list-length sweep: 1 ... 65,536 uniform indices, rows of "
+                                                 "512 B, 4 KiB, 64 KiB and 1 MiB in pinned mapped host memory"},
+                          "link": {"measured_h2d_gbps": round(link_peak, 2), "nominal_gbps": nominal},
+                          "list_length_sweep": pts}))
+        return
     if args.config == 8:
         res = run_pipeline(args, z, wl, np, torch, link_peak)
         print(json.dumps({"metric": "ms per minibatch (list copy + gather + synthetic compute)",

@@ -96,6 +96,11 @@ typedef struct zcg_launch_opts {
                       writes with narrower / unaligned stores; 2 narrows the loads instead.
                       With wide loads, up to vec_bytes-1 bytes next to a row end, inside
                       the same aligned vec_bytes block, are read and dropped.            */
+  int row_splits;  /* rows wider than one wave pass: number of wavefronts that share a
+                      row, each taking one contiguous piece (1 = one wavefront per row,
+                      up to 4096). Default: 1 for long lists; short lists of long rows
+                      are split until there is enough work in flight to fill the link.
+                      HALFLINE and NAIVE do not split.                                  */
 } zcg_launch_opts;
 
 /* How one gather call is laid out on the GPU; filled by zcg_plan_gather. */
@@ -110,6 +115,7 @@ typedef struct zcg_plan {
   int nt_stores;   /* 0 / 1                                                            */
   int blocks;      /* grid size, blocks of 256 lanes                                   */
   int store_bytes; /* alignment the stores can rely on; < vec_bytes means shifted stores */
+  int row_splits;  /* wavefronts per row (rows wider than one wave pass), else 1          */
 } zcg_plan;
 
 /* ---- errors ------------------------------------------------------------ */

@@ -102,7 +102,7 @@ template <int W, int U, int NTL, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_wide(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
                 const int64_t* __restrict__ order, int64_t n_idx, uint8_t* __restrict__ out,
-                int64_t row_bytes, unsigned line_mask) {
+                int64_t row_bytes, unsigned line_mask, int64_t splits, int64_t piece_bytes) {
   typedef typename vec_of<W>::type vec;
   const unsigned lane = threadIdx.x & (kWave - 1);
   const int64_t n_waves = ((int64_t)gridDim.x * kBlock) / kWave;
@@ -110,20 +110,28 @@ zcg_k_rows_wide(const uint8_t* __restrict__ table, const int64_t* __restrict__ i
   constexpr int64_t kStep = (int64_t)kWave * W;
   const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
 
-  for (int64_t k = wave; k < n_idx; k += n_waves) {
-    const int64_t r = order ? order[k] : k;  // position in the list = output row
+  // work item k = (row k / splits, piece k % splits); piece_bytes is a multiple of kStep * U
+  for (int64_t k = wave; k < n_idx * splits; k += n_waves) {
+    int64_t rk = k, piece = 0;
+    if (splits > 1) {
+      rk = k / splits;
+      piece = k - rk * splits;
+    }
+    const int64_t r = order ? order[rk] : rk;  // position in the list = output row
     const uint8_t* src = table + idx[r] * row_bytes;
     const int64_t mis = (int64_t)((uintptr_t)src & line_mask);
     const int64_t span = mis + row_bytes;
     const int64_t src_shift = -mis;                 // chunk c of the span is src[c - mis]
     const int64_t dst_shift = r * row_bytes - mis;  // and lands at out[r*row_bytes + c - mis]
-    for (int64_t c0 = (int64_t)lane * W; c0 < span; c0 += kStep * U) {
+    const int64_t c_lo = piece * piece_bytes;
+    const int64_t c_hi = (splits > 1 && c_lo + piece_bytes < span) ? c_lo + piece_bytes : span;
+    for (int64_t c0 = c_lo + (int64_t)lane * W; c0 < c_hi; c0 += kStep * U) {
       vec v[U];
       bool ok[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int64_t c = c0 + (int64_t)u * kStep;
-        ok[u] = (c >= mis) && (c < span);
+        ok[u] = (c >= mis) && (c < c_hi);
         v[u] = load_chunk<W, NTL>(ok[u] ? src + (src_shift + c) : dummy);
       }
 #pragma unroll
@@ -220,7 +228,7 @@ template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_wide_shift(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
                       const int64_t* __restrict__ order, int64_t n_idx, uint8_t* __restrict__ out,
-                      int64_t row_bytes, unsigned line_mask) {
+                      int64_t row_bytes, unsigned line_mask, int64_t splits, int64_t piece_bytes) {
   typedef typename vec_of<W>::type vec;
   const unsigned lane = threadIdx.x & (kWave - 1);
   const int64_t n_waves = ((int64_t)gridDim.x * kBlock) / kWave;
@@ -228,19 +236,29 @@ zcg_k_rows_wide_shift(const uint8_t* __restrict__ table, const int64_t* __restri
   constexpr int64_t kStep = (int64_t)kWave * W;
   const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
 
-  for (int64_t k = wave; k < n_idx; k += n_waves) {
-    const int64_t r = order ? order[k] : k;
+  // work item k = (row k / splits, piece k % splits) as in zcg_k_rows_wide
+  for (int64_t k = wave; k < n_idx * splits; k += n_waves) {
+    int64_t rk = k, piece = 0;
+    if (splits > 1) {
+      rk = k / splits;
+      piece = k - rk * splits;
+    }
+    const int64_t r = order ? order[rk] : rk;
     const uint8_t* src = table + idx[r] * row_bytes;
     const int64_t mis = (int64_t)((uintptr_t)src & line_mask);
     uint8_t* out_row = out + r * row_bytes;
+    // this piece of the line-aligned span, as offsets relative to the row start
+    const int64_t off_lo = piece * piece_bytes - mis;
+    const int64_t off_hi = (splits > 1 && off_lo + piece_bytes < row_bytes) ? off_lo + piece_bytes
+                                                                           : row_bytes;
     // off walks the chunks of the line-aligned span, relative to the row start
-    for (int64_t off0 = (int64_t)lane * W - mis; off0 < row_bytes; off0 += kStep * U) {
+    for (int64_t off0 = off_lo + (int64_t)lane * W; off0 < off_hi; off0 += kStep * U) {
       vec v[U];
       bool ok[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int64_t off = off0 + (int64_t)u * kStep;
-        ok[u] = (off > -(int64_t)W) && (off < row_bytes);
+        ok[u] = (off > -(int64_t)W) && (off < off_hi);
         v[u] = load_chunk<W, 0>(ok[u] ? src + off : dummy);
       }
 #pragma unroll
@@ -468,11 +486,23 @@ __global__ void zcg_k_chase(const uint64_t* __restrict__ chain, int64_t stride_w
   *result = p;
 }
 
+// Bytes of a row's line-aligned span that one wavefront takes when p.row_splits wavefronts
+// share the row: whole passes of 64 * W * U bytes, so every piece runs the same loop, and
+// enough of them to cover the longest span (row_bytes plus less than a line).
+inline int64_t piece_bytes_of(const zcg_plan& p, int64_t row_bytes, int W, int U) {
+  const int64_t splits = p.row_splits > 1 ? p.row_splits : 1;
+  const int64_t pass = (int64_t)kWave * W * U;
+  const int64_t per = (row_bytes + p.line_bytes + splits - 1) / splits;
+  return (per + pass - 1) / pass * pass;
+}
+
 template <int W, int U>
 hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* idx, const int64_t* order, int64_t n_idx,
                        uint8_t* out, int64_t row_bytes, hipStream_t s) {
   const unsigned mask = (p.variant == ZCG_VARIANT_ALIGNED) ? (unsigned)(p.line_bytes - 1) : 0u;
   const dim3 grid((unsigned)p.blocks), block(kBlock);
+  const int64_t splits = p.row_splits > 1 ? p.row_splits : 1;
+  const int64_t piece = piece_bytes_of(p, row_bytes, W, U);
   if constexpr (W >= 4) {
     if (p.variant == ZCG_VARIANT_HALFLINE) {
       if (p.iters == 1) {
@@ -498,7 +528,7 @@ hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* i
                                                                  row_bytes, p.log2_group, mask); \
     else                                                                                        \
       zcg_k_rows_wide<W, U, NTL, NTS><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,    \
-                                                               row_bytes, mask);                \
+                                                               row_bytes, mask, splits, piece); \
   } while (0)
   switch (p.nt_loads * 2 + (p.nt_stores ? 1 : 0)) {
     case 0: ZCG_LAUNCH(0, false); break;
@@ -529,6 +559,8 @@ hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* 
                         uint8_t* out, int64_t row_bytes, hipStream_t s) {
   const unsigned mask = (unsigned)(p.line_bytes - 1);
   const dim3 grid((unsigned)p.blocks), block(kBlock);
+  const int64_t splits = p.row_splits > 1 ? p.row_splits : 1;
+  const int64_t piece = piece_bytes_of(p, row_bytes, W, U);
   if constexpr (WS >= 4) {
     if (p.variant == ZCG_VARIANT_HALFLINE) {
       if (p.iters == 1) {
@@ -559,10 +591,10 @@ hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* 
   } else {
     if (p.nt_stores)
       zcg_k_rows_wide_shift<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, order, n_idx, out, row_bytes,
-                                                                    mask);
+                                                                    mask, splits, piece);
     else
       zcg_k_rows_wide_shift<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
-                                                                     row_bytes, mask);
+                                                                     row_bytes, mask, splits, piece);
   }
   return hipGetLastError();
 }

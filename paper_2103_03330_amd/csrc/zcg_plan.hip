@@ -52,6 +52,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   if (max_blocks < 1 || o.nt_loads < 0 || o.nt_loads > 3 || o.nt_stores < 0 || o.nt_stores > 2)
     return ZCG_EINVAL;
   if (vec_cap < elem || o.shifted_stores < 0 || o.shifted_stores > 2) return ZCG_EINVAL;
+  if (o.row_splits < 0 || o.row_splits > 4096) return ZCG_EINVAL;
   int min_lg = 0;
   if (o.group_lanes) {
     if (o.group_lanes < 1 || o.group_lanes > kWave || (o.group_lanes & (o.group_lanes - 1)))
@@ -81,12 +82,17 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     // Long unaligned rows over the host link: one half-line read per ~8+ lines is a net gain
     // (measured +2...4 % on 1,032...2,408-byte rows with 8- or 16-byte lanes); on short rows
     // it is a loss, with 4-byte lanes it is neutral.
-    if (variant == ZCG_VARIANT_ALIGNED && host_resident && row_bytes >= 1024 &&
+    // A short list of long rows is split over several wavefronts per row (below), which the
+    // half-line kernel does not do: filling the link matters more there than 64 bytes per row.
+    const bool will_split = o.row_splits ? o.row_splits > 1
+                                         : (n_idx < 2048 && row_bytes >= (int64_t)8 * kWave * vec_cap * unroll);
+    if (variant == ZCG_VARIANT_ALIGNED && host_resident && row_bytes >= 1024 && !will_split &&
         (w >= 8 || (w >= 4 && vec_cap >= 8 && o.shifted_stores != 2)))
       variant = ZCG_VARIANT_HALFLINE, line = 128;
   }
 
   plan->variant = variant;
+  plan->row_splits = 1;
   plan->line_bytes = line;
   plan->unroll = unroll;
   plan->nt_loads = ntl;
@@ -122,7 +128,27 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
       want_blocks = ((groups << lg) + kBlock - 1) / kBlock;
     } else {
       plan->log2_group = 6;
-      want_blocks = (n_idx * kWave + kBlock - 1) / kBlock;
+      // One wavefront per row keeps only unroll * 64 * vec_bytes bytes of that row in flight
+      // (measured: 0.7 GB/s per row over the host link), so a short list of long rows cannot
+      // fill the link. Then several wavefronts share a row, each taking a contiguous piece of
+      // at least 4 passes, until about 4096 (host) / 16384 (HBM) wavefronts have work.
+      int splits = 1;
+      if (variant != ZCG_VARIANT_HALFLINE) {
+        const int64_t pass = (int64_t)kWave * wl * unroll;
+        const int64_t most = (worst_span + pass - 1) / pass;  // pieces of one pass each
+        if (o.row_splits) {
+          splits = (int)(o.row_splits < most ? o.row_splits : most);
+        } else {
+          const int64_t target = host_resident ? 4096 : 16384;
+          int64_t want = n_idx > 0 ? target / n_idx : 1;
+          const int64_t cap = most / 4;
+          if (want > cap) want = cap;
+          if (want > 4096) want = 4096;
+          splits = want > 1 ? (int)want : 1;
+        }
+      }
+      plan->row_splits = splits;
+      want_blocks = (n_idx * splits * kWave + kBlock - 1) / kBlock;
     }
   }
   if (want_blocks < 1) want_blocks = 1;

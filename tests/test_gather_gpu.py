@@ -103,6 +103,13 @@ def test_launch_knobs_do_not_change_the_result(dim, dtype):
             # one block only: the grid-stride loop does all the work
             o = z.LaunchOpts(variant=variant, max_blocks=1)
             assert_same_bits(run_gather(table, idx, dtype, o), want, "max_blocks=1")
+            # several wavefronts per row (rows wider than one wave pass; else the knob is moot)
+            for splits, unroll, vec in ((2, 1, 0), (3, 2, 0), (7, 1, 4), (64, 1, 2), (4096, 1, 1)):
+                if vec and vec < table.elem_bytes:
+                    continue
+                o = z.LaunchOpts(variant=variant, row_splits=splits, unroll=unroll, vec_bytes=vec,
+                                 max_blocks=0 if splits != 3 else 5)
+                assert_same_bits(run_gather(table, idx, dtype, o), want, f"splits{splits} u{unroll} v{vec}")
         o = z.LaunchOpts(variant=z.VARIANT_NAIVE, max_blocks=3, nt_loads=1)
         assert_same_bits(run_gather(table, idx, dtype, o), want, "naive 3 blocks")
     finally:
@@ -405,11 +412,15 @@ def test_very_wide_rows_and_first_last_row(n_rows, dim, dtype):
         lists = [np.array([n_rows - 1], np.int64), np.array([0], np.int64),
                  np.array([n_rows - 1, 0, n_rows - 1, 0, 1], np.int64),
                  wl.uniform_indices(67, n_rows, seed=3)]
+        probe = torch.zeros((1, dim), dtype=TORCH_DT[dtype], device="cuda")
+        assert z.plan_gather(table, 1, probe)["row_splits"] > 1  # a short list of long rows is split
+        assert z.plan_gather(table, 1_000_000, probe)["row_splits"] == 1
         for idx in lists:
             want = oracle_gather(host, idx)
             for variant in ALL_VARIANTS:
-                got = run_gather(table, idx, dtype, z.LaunchOpts(variant=variant))
-                assert_same_bits(got, want, f"{dtype} dim={dim} n_idx={len(idx)} variant={variant}")
+                for splits in (0, 1, 13):
+                    got = run_gather(table, idx, dtype, z.LaunchOpts(variant=variant, row_splits=splits))
+                    assert_same_bits(got, want, f"{dtype} dim={dim} n_idx={len(idx)} variant={variant} splits={splits}")
             idx_dev = torch.from_numpy(idx).cuda()
             order = torch.from_numpy(np.argsort(idx, kind="stable")).cuda()
             out = torch.zeros((len(idx), dim), dtype=TORCH_DT[dtype], device="cuda")

@@ -162,9 +162,21 @@ def test_plan_picks_width_group_and_variant():
     p = plan(100, "f32", n_idx=3)
     assert p["blocks"] == 1
     for bad in (dict(unroll=3), dict(line_bytes=48), dict(vec_bytes=2), dict(vec_bytes=3), dict(variant=5),
-                dict(nt_loads=4), dict(shifted_stores=3)):
+                dict(nt_loads=4), dict(shifted_stores=3), dict(row_splits=-1), dict(row_splits=4097)):
         with pytest.raises(z.ZcgError):
             plan(100, "f32", **bad)
+
+
+def test_plan_splits_long_rows_of_short_lists():
+    p = plan(16384, "f32", n_idx=16)  # 64 KiB rows, 16 of them: 4 passes of 4 KiB per wavefront
+    assert (p["iters"] > 1, p["row_splits"], p["blocks"]) == (True, 4, 16)
+    assert plan(16384, "f32", n_idx=100_000)["row_splits"] == 1  # long list: a wavefront per row
+    assert plan(16384, "f32", n_idx=16, row_splits=1)["row_splits"] == 1
+    assert plan(16384, "f32", n_idx=16, row_splits=4096)["row_splits"] == 16  # at least one pass each
+    assert plan(602, "f32", n_idx=4)["row_splits"] == 1  # too short to be worth splitting
+    assert plan(602, "f32", n_idx=4, row_splits=2, unroll=1)["row_splits"] == 2
+    assert plan(100, "f32", n_idx=4, row_splits=8)["row_splits"] == 1  # one pass covers the row
+    assert plan(16384, "f32", n_idx=16, variant=z.VARIANT_HALFLINE, row_splits=8)["row_splits"] == 1
 
 
 def covered_bytes(row_bytes, src_addr, p):
