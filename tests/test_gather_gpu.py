@@ -202,6 +202,17 @@ def test_hbm_resident_table_and_noncoherent_host_table():
     for variant in ALL_VARIANTS:
         assert_same_bits(run_gather(t, idx, "f32", z.LaunchOpts(variant=variant)), want, "hbm")
     t.close()
+    # a short list of long rows out of HBM: the rows are shared among wavefronts
+    wide = wl.make_table(30, 50_001, "f32", seed=22)
+    dev_wide = torch.from_numpy(wide).cuda()
+    t = z.table_from_device(dev_wide, 30, 50_001, "f32")
+    short = np.array([29, 0, 7, 29], np.int64)
+    probe = torch.zeros((4, 50_001), dtype=torch.float32, device="cuda")
+    assert z.plan_gather(t, 4, probe)["row_splits"] > 1
+    for variant in ALL_VARIANTS:
+        assert_same_bits(run_gather(t, short, "f32", z.LaunchOpts(variant=variant)),
+                         oracle_gather(wide, short), "hbm wide")
+    t.close()
     t = host_table(n_rows, dim, "f32", seed=21, flags=z.ALLOC_NONCOHERENT)
     for variant in ALL_VARIANTS:
         assert_same_bits(run_gather(t, idx, "f32", z.LaunchOpts(variant=variant)), want, "noncoh")
