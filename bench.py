@@ -792,6 +792,10 @@ def main():
                                        "what": "whole 128 B lines spanned by each row (64 B half lines "
                                                "for row ends under HALFLINE)"},
                      "kernel_ms_avg": round(avg_kernel_ms, 4),
+                     "hbm_side": {"bytes_per_row": rb + 8, "achieved_gbps": round(achieved * (rb + 8) / rb, 1),
+                                  "peak_gbps": 8000.0, "frac": round(achieved * (rb + 8) / rb / 8000.0, 5),
+                                  "note": "rows written + index list read: HBM is nowhere near its limit, "
+                                          "which is why the host link is the roofline of this path"},
                      "peak_is": "measured pinned hipMemcpyAsync host->device (1 GiB, median of 10)",
                      "algorithmic_bytes_per_row": rb,
                      "ceiling_note": "the link moves whole 128 B lines: a row costs "
