@@ -356,6 +356,16 @@ int zcg_pipeline_destroy(zcg_pipeline* p);
  */
 int zcg_measure_host_read_latency(int device, int64_t hops, double* microseconds);
 
+/*
+ * The rate at which GPU lanes themselves can pull consecutive bytes of mapped
+ * host memory into HBM (the ceiling of any zero-copy gather): median over
+ * `reps` runs of a plain streaming kernel with the gather's access shape over a
+ * fresh mapped buffer of `bytes` bytes (a multiple of 4096), in GB/s (1e9
+ * bytes). Compare with zcg_measure_h2d, the copy engine's rate over the same
+ * link. SYNCHRONOUS; allocates and frees its buffers.
+ */
+int zcg_measure_host_stream_read(int device, int64_t bytes, int reps, double* gb_per_s);
+
 /* Pinned host scratch for callers without another allocator (staging buffers). */
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr);
 int zcg_pinned_free(void* host_ptr);

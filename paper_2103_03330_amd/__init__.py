@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     alloc_table, device_cu_count, stream_create_cu_mask, stream_destroy, synthetic_compute,
     cpu_gather_memcpy, cpu_gather_memcpy_chunked, gather, gather_ex, gather_ordered, gather_variant,
     make_order, order_workspace_bytes,
-    last_hip_error, load_library, measure_h2d, measure_host_read_latency, pipeline_create, pinned_alloc, pinned_free, plan_gather,
+    last_hip_error, load_library, measure_h2d, measure_host_read_latency, measure_host_stream_read, pipeline_create, pinned_alloc, pinned_free, plan_gather,
     register_table, strerror, table_from_device, unregister_table, validate_indices, version,
 )
 from .unified import UnifiedTensor, to_unified  # noqa: F401,E402

@@ -40,7 +40,7 @@ EXPORTS = [
     "zcg_synthetic_compute", "zcg_pipeline_create", "zcg_pipeline_submit", "zcg_pipeline_submit_wait",
     "zcg_pipeline_finish", "zcg_pipeline_next", "zcg_pipeline_acquire",
     "zcg_pipeline_release", "zcg_pipeline_destroy", "zcg_gather_ordered",
-    "zcg_order_workspace_bytes", "zcg_make_order", "zcg_measure_host_read_latency",
+    "zcg_order_workspace_bytes", "zcg_make_order", "zcg_measure_host_read_latency", "zcg_measure_host_stream_read",
 ]
 
 
@@ -125,6 +125,7 @@ def load_library() -> ctypes.CDLL:
         "zcg_order_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
         "zcg_make_order": (i32, [vp, i64, i64, vp, vp, i64, vp]),
         "zcg_measure_host_read_latency": (i32, [i32, i64, ctypes.POINTER(ctypes.c_double)]),
+        "zcg_measure_host_stream_read": (i32, [i32, i64, i32, ctypes.POINTER(ctypes.c_double)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -478,3 +479,11 @@ def measure_host_read_latency(hops: int = 20000, device: int = 0) -> float:
     _check(load_library().zcg_measure_host_read_latency(device, hops, ctypes.byref(us)),
            "zcg_measure_host_read_latency")
     return float(us.value)
+
+
+def measure_host_stream_read(n_bytes: int = 256 << 20, reps: int = 10, device: int = 0) -> float:
+    """GB/s at which GPU lanes stream consecutive bytes of mapped host memory into HBM."""
+    g = ctypes.c_double(0.0)
+    _check(load_library().zcg_measure_host_stream_read(device, n_bytes, reps, ctypes.byref(g)),
+           "zcg_measure_host_stream_read")
+    return float(g.value)

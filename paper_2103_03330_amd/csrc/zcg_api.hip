@@ -402,6 +402,47 @@ int zcg_measure_host_read_latency(int device, int64_t hops, double* microseconds
   return ZCG_OK;
 }
 
+int zcg_measure_host_stream_read(int device, int64_t bytes, int reps, double* gb_per_s) {
+  if (device < 0 || bytes < 4096 || bytes % 4096 || reps < 1 || reps > 1000 || !gb_per_s)
+    return ZCG_EINVAL;
+  *gb_per_s = 0.0;
+  DeviceScope scope(device);
+  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
+  void *host = nullptr, *dev_view = nullptr, *dst = nullptr;
+  hipStream_t s = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  std::vector<float> ms;
+  hipError_t e = hipHostMalloc(&host, (size_t)bytes, hipHostMallocMapped | hipHostMallocCoherent);
+  if (e == hipSuccess) e = hipHostGetDevicePointer(&dev_view, host, 0);
+  if (e == hipSuccess) e = hipMalloc(&dst, (size_t)bytes);
+  if (e == hipSuccess) e = hipStreamCreate(&s);
+  if (e == hipSuccess) e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e == hipSuccess) {
+    for (int64_t i = 0; i < bytes; i += 4096) static_cast<volatile char*>(host)[i] = (char)i;
+    e = zcg_launch_stream_read(s, dev_view, dst, bytes, 2048);  // warm-up
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+  }
+  for (int r = 0; r < reps && e == hipSuccess; ++r) {
+    e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = zcg_launch_stream_read(s, dev_view, dst, bytes, 2048);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float t = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+    if (e == hipSuccess) ms.push_back(t);
+  }
+  if (e1) (void)hipEventDestroy(e1);
+  if (e0) (void)hipEventDestroy(e0);
+  if (s) (void)hipStreamDestroy(s);
+  if (dst) (void)hipFree(dst);
+  if (host) (void)hipHostFree(host);
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  std::sort(ms.begin(), ms.end());
+  *gb_per_s = (double)bytes / ((double)ms[ms.size() / 2] * 1e-3) / 1e9;
+  return ZCG_OK;
+}
+
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr) {
   if (bytes <= 0 || !host_ptr) return ZCG_EINVAL;
   *host_ptr = nullptr;

@@ -33,6 +33,8 @@ hipError_t zcg_launch_gather(const zcg_plan& plan, const void* table, const int6
                              hipStream_t stream);
 hipError_t zcg_launch_chase(hipStream_t stream, const uint64_t* chain, int64_t stride_words,
                             int64_t hops, uint64_t* result);
+hipError_t zcg_launch_stream_read(hipStream_t stream, const void* src, void* dst, int64_t bytes,
+                                  int blocks);
 hipError_t zcg_launch_synthetic_compute(hipStream_t stream, int blocks, int64_t iters, float* sink);
 hipError_t zcg_launch_validate(const int64_t* idx, int64_t n_idx, int64_t n_rows,
                                unsigned long long* n_bad_dev, hipStream_t stream);

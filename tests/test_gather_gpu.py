@@ -389,6 +389,9 @@ def test_link_probes_give_sane_numbers():
     rtt = z.measure_host_read_latency(4000)
     assert 0.2 < rtt < 50.0  # microseconds per dependent read of mapped host memory
     assert 5.0 < z.measure_h2d(64 << 20, 3) < 200.0  # GB/s
+    assert 5.0 < z.measure_host_stream_read(64 << 20, 3) < 200.0  # GB/s
+    with pytest.raises(z.ZcgError):
+        z.measure_host_stream_read(1000, 3)  # not a multiple of a page
 
 
 @pytest.mark.parametrize("flags", [z.ALLOC_DEFAULT, z.ALLOC_NONCOHERENT])
