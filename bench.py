@@ -522,6 +522,42 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
             "cases": cases}
 
 
+def run_request_blocks(args, z, wl, np, torch):
+    """Which unit the link's read requests come in: random rows of 128 ... 512 bytes (row pitch =
+    row size) read from a mapped base that is a multiple of 256 bytes, then from the same base
+    plus 128 bytes, with the launch shape of host-resident tables in both cases."""
+    n_rows, n_idx = 4_000_000, 400_000
+    cur = torch.cuda.current_stream()
+    pts = []
+    for dim in (128, 96, 64, 32):
+        rb = dim * 4
+        base = z.alloc_table(n_rows + 2, dim, "f32")
+        idx = torch.from_numpy(wl.uniform_indices(n_idx, n_rows, seed=5)).cuda()
+        out = torch.empty((n_idx, dim), dtype=torch.float32, device="cuda")
+        for off in (0, 128):
+            view = z.table_from_device(base.device_ptr + off, n_rows, dim, "f32")
+            o = z.LaunchOpts(unroll=2, nt_loads=2, max_blocks=2048 if rb > 128 else 8192,
+                             vec_bytes=8 if rb > 128 else 16, group_lanes=64 if rb > 128 else 16)
+            for _ in range(3):
+                z.gather_ex(view, idx, out, o, stream=cur)
+            torch.cuda.synchronize()
+            ms = []
+            for _ in range(20):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(cur)
+                z.gather_ex(view, idx, out, o, stream=cur)
+                e1.record(cur)
+                e1.synchronize()
+                ms.append(e0.elapsed_time(e1))
+            t = float(np.median(ms))
+            pts.append({"row_bytes": rb, "base_offset": off, "gbps": round(n_idx * rb / t / 1e6, 2),
+                        "rows_per_s": round(n_idx / t * 1e3)})
+            print(f"# {pts[-1]}", file=sys.stderr, flush=True)
+            view.close()
+        base.close()
+    return pts
+
+
 def run_list_length(args, z, wl, np, torch, link_peak):
     """Gather time against list length for rows of 512 B ... 1 MiB: where the launch and the first
     round trip dominate, where the link fills, and what giving several wavefronts to one long
@@ -650,7 +686,7 @@ def main():
                                                  "dedup, power-law graph avg degree 32; 8 minibatches",
                                      "rows_per_step_avg": avg_rows},
                           "link": {"measured_h2d_gbps": round(link_peak, 2), "nominal_gbps": nominal},
-                          "sweep": pts}))
+                          "sweep": pts, "request_blocks": run_request_blocks(args, z, wl, np, torch)}))
         return
 
     cfg, table, lists, build_info = build_workload(z, wl, args.config, n_batches, z.ALLOC_DEFAULT,

@@ -59,8 +59,8 @@ extern "C" {
 
 /* ---- gather kernels (zcg_gather_variant / zcg_gather_ex) --------------- */
 #define ZCG_VARIANT_AUTO 0    /* rows shorter than a line or made of whole lines: ROWVEC;
-                                 else ALIGNED, or HALFLINE for host-resident rows of at
-                                 least 1 KiB with 8-byte granularity                    */
+                                 else ALIGNED, or HALFLINE for host-resident rows of more
+                                 than a line with at least 4-byte granularity           */
 #define ZCG_VARIANT_NAIVE 1   /* one element per lane over the flat output, no alignment
                                  care: the paper's baseline kernel (Section 4.1.2 (c))  */
 #define ZCG_VARIANT_ROWVEC 2  /* a lane group per row, widest vector, loads start at the
@@ -101,6 +101,11 @@ typedef struct zcg_launch_opts {
                       up to 4096). Default: 1 for long lists; short lists of long rows
                       are split until there is enough work in flight to fill the link.
                       HALFLINE and NAIVE do not split.                                  */
+  int half_ends;   /* HALFLINE: 1 = every row end that fits half a line goes through a
+                      64-byte scalar read; 2 = only ends whose line would otherwise be
+                      requested alone (its partner in the 256-byte aligned pair is not
+                      part of the row), which never adds a link request. Default: 1 for
+                      rows of 1 KiB and more, 2 for shorter rows.                       */
 } zcg_launch_opts;
 
 /* How one gather call is laid out on the GPU; filled by zcg_plan_gather. */
@@ -116,6 +121,7 @@ typedef struct zcg_plan {
   int blocks;      /* grid size, blocks of 256 lanes                                   */
   int store_bytes; /* alignment the stores can rely on; < vec_bytes means shifted stores */
   int row_splits;  /* wavefronts per row (rows wider than one wave pass), else 1          */
+  int half_ends;   /* HALFLINE: 1 all row ends, 2 lone lines only; else 0                 */
 } zcg_plan;
 
 /* ---- errors ------------------------------------------------------------ */

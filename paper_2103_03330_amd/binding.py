@@ -50,7 +50,7 @@ class LaunchOpts(ctypes.Structure):
                 ("line_bytes", ctypes.c_int), ("nt_loads", ctypes.c_int),
                 ("nt_stores", ctypes.c_int), ("vec_bytes", ctypes.c_int),
                 ("group_lanes", ctypes.c_int), ("shifted_stores", ctypes.c_int),
-                ("row_splits", ctypes.c_int)]
+                ("row_splits", ctypes.c_int), ("half_ends", ctypes.c_int)]
 
 
 class Plan(ctypes.Structure):
@@ -59,7 +59,8 @@ class Plan(ctypes.Structure):
                 ("log2_group", ctypes.c_int), ("iters", ctypes.c_int), ("unroll", ctypes.c_int),
                 ("line_bytes", ctypes.c_int), ("nt_loads", ctypes.c_int),
                 ("nt_stores", ctypes.c_int), ("blocks", ctypes.c_int),
-                ("store_bytes", ctypes.c_int), ("row_splits", ctypes.c_int)]
+                ("store_bytes", ctypes.c_int), ("row_splits", ctypes.c_int),
+                ("half_ends", ctypes.c_int)]
 
     def as_dict(self) -> dict:
         return {k: getattr(self, k) for k, _ in self._fields_}

@@ -302,15 +302,25 @@ struct RowSplit {
   bool has_head, has_tail;
 };
 
-__device__ __forceinline__ RowSplit split_row(uint64_t S, uint64_t row_bytes) {
+// only_lone: take an end through the scalar path only if the line it sits in would otherwise
+// be requested alone. Measured: the link fetches 256-byte aligned pairs of lines as one
+// request when a wave asks for both, and a lone line, a pair and a 64-byte scalar read each
+// cost one request; so replacing a lone line saves 64 bytes for free, while replacing a line
+// whose partner is part of the row turns one request into two.
+__device__ __forceinline__ RowSplit split_row(uint64_t S, uint64_t row_bytes, bool only_lone) {
   RowSplit p;
   const uint64_t E = S + row_bytes;
-  p.has_head = (S & 127u) >= 64u;
   const uint64_t next_line = (S | 127u) + 1u;
+  // first line: alone if it is the upper line of its pair, or the row ends inside it
+  const bool head_lone = ((S >> 7) & 1u) != 0u || E <= next_line;
+  p.has_head = (S & 127u) >= 64u && (!only_lone || head_lone);
   p.vs = p.has_head ? (E < next_line ? E : next_line) : S;
   p.head_addr = S & ~(uint64_t)63u;
   const uint64_t last_line = (E - 1u) & ~(uint64_t)127u;
-  p.has_tail = (p.vs < E) && (((E - 1u) & 127u) < 64u);
+  // last line: alone if it is the lower line of its pair, or nothing before it is left to the
+  // vector loads
+  const bool tail_lone = ((last_line >> 7) & 1u) == 0u || p.vs >= last_line;
+  p.has_tail = (p.vs < E) && (((E - 1u) & 127u) < 64u) && (!only_lone || tail_lone);
   p.tail_addr = last_line;
   p.ve = p.has_tail ? (p.vs > last_line ? p.vs : last_line) : E;
   return p;
@@ -341,7 +351,8 @@ __device__ __forceinline__ void move_pieces(const RowSplit& sp, uint64_t S, uint
 template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
-                       int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g) {
+                       int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g,
+                       int only_lone) {
   typedef typename vec_of<W>::type vec;
   const unsigned wave_lane = threadIdx.x & (kWave - 1);
   const unsigned lane = threadIdx.x & ((1u << log2_g) - 1u);
@@ -368,7 +379,7 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
       const int64_t r = wbase + my_group + (int64_t)u * n_groups;
       const uint64_t S = (uint64_t)(uintptr_t)(table + row_id[u] * row_bytes);
       src[u] = S;
-      const RowSplit sp = split_row(S, (uint64_t)row_bytes);
+      const RowSplit sp = split_row(S, (uint64_t)row_bytes, only_lone != 0);
       const uint64_t a = (S & ~(uint64_t)127u) + (uint64_t)lane_off;  // line-aligned lane mapping
       ok[u] = (r < n_idx) && (a + W > sp.vs) && (a < sp.ve);
       // pointer formed from `table` so that the load stays a global (not flat) access
@@ -381,7 +392,7 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
         const int64_t r = wbase + g + (int64_t)u * n_groups;  // uniform
         if (r < n_idx) {
           const uint64_t S = uniform_u64(src[u], g << log2_g);
-          const RowSplit sp = split_row(S, (uint64_t)row_bytes);
+          const RowSplit sp = split_row(S, (uint64_t)row_bytes, only_lone != 0);
           if (sp.has_head || sp.has_tail)
             move_pieces(sp, S, (uint64_t)row_bytes, out + r * row_bytes, wave_lane);
         }
@@ -391,7 +402,7 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
     for (int u = 0; u < U; ++u) {
       if (ok[u]) {
         const int64_t r = wbase + my_group + (int64_t)u * n_groups;
-        const RowSplit sp = split_row(src[u], (uint64_t)row_bytes);
+        const RowSplit sp = split_row(src[u], (uint64_t)row_bytes, only_lone != 0);
         const int64_t off = (int64_t)((src[u] & ~(uint64_t)127u) + (uint64_t)lane_off - src[u]);
         store_shifted<W, WS, NTS>(out + r * row_bytes, off, (int64_t)(sp.vs - src[u]),
                                   (int64_t)(sp.ve - src[u]), v[u]);
@@ -403,7 +414,7 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
 template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
-                     int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes) {
+                     int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int only_lone) {
   typedef typename vec_of<W>::type vec;
   const unsigned lane = threadIdx.x & (kWave - 1);
   const int64_t n_waves = ((int64_t)gridDim.x * kBlock) / kWave;
@@ -413,7 +424,7 @@ zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restric
 
   for (int64_t r = wave; r < n_idx; r += n_waves) {
     const uint64_t S = uniform_u64((uint64_t)(uintptr_t)(table + idx[r] * row_bytes), 0);
-    const RowSplit sp = split_row(S, (uint64_t)row_bytes);
+    const RowSplit sp = split_row(S, (uint64_t)row_bytes, only_lone != 0);
     uint8_t* out_row = out + r * row_bytes;
     if (sp.has_head || sp.has_tail) move_pieces(sp, S, (uint64_t)row_bytes, out_row, lane);
     const uint64_t a0 = (sp.vs & ~(uint64_t)127u) + (uint64_t)lane * W;  // line-aligned lane mapping
@@ -526,20 +537,21 @@ hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* i
   const dim3 grid((unsigned)p.blocks), block(kBlock);
   const int64_t splits = p.row_splits > 1 ? p.row_splits : 1;
   const int64_t piece = piece_bytes_of(p, row_bytes, W, U);
+  const int lone = p.half_ends == 2 ? 1 : 0;
   if constexpr (W >= 4) {
     if (p.variant == ZCG_VARIANT_HALFLINE) {
       if (p.iters == 1) {
         if (p.nt_stores)
           zcg_k_rows_narrow_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
-                                                                     row_bytes, p.log2_group);
+                                                                     row_bytes, p.log2_group, lone);
         else
           zcg_k_rows_narrow_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
-                                                                      row_bytes, p.log2_group);
+                                                                      row_bytes, p.log2_group, lone);
       } else {
         if (p.nt_stores)
-          zcg_k_rows_wide_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes);
+          zcg_k_rows_wide_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes, lone);
         else
-          zcg_k_rows_wide_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes);
+          zcg_k_rows_wide_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes, lone);
       }
       return hipGetLastError();
     }
@@ -584,22 +596,23 @@ hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* 
   const dim3 grid((unsigned)p.blocks), block(kBlock);
   const int64_t splits = p.row_splits > 1 ? p.row_splits : 1;
   const int64_t piece = piece_bytes_of(p, row_bytes, W, U);
+  const int lone = p.half_ends == 2 ? 1 : 0;
   if constexpr (WS >= 4) {
     if (p.variant == ZCG_VARIANT_HALFLINE) {
       if (p.iters == 1) {
         if (p.nt_stores)
           zcg_k_rows_narrow_half<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
-                                                                         row_bytes, p.log2_group);
+                                                                         row_bytes, p.log2_group, lone);
         else
           zcg_k_rows_narrow_half<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
-                                                                          row_bytes, p.log2_group);
+                                                                          row_bytes, p.log2_group, lone);
       } else {
         if (p.nt_stores)
           zcg_k_rows_wide_half<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
-                                                                       row_bytes);
+                                                                       row_bytes, lone);
         else
           zcg_k_rows_wide_half<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
-                                                                        row_bytes);
+                                                                        row_bytes, lone);
       }
       return hipGetLastError();
     }

@@ -53,6 +53,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     return ZCG_EINVAL;
   if (vec_cap < elem || o.shifted_stores < 0 || o.shifted_stores > 2) return ZCG_EINVAL;
   if (o.row_splits < 0 || o.row_splits > 4096) return ZCG_EINVAL;
+  if (o.half_ends < 0 || o.half_ends > 2) return ZCG_EINVAL;
   int min_lg = 0;
   if (o.group_lanes) {
     if (o.group_lanes < 1 || o.group_lanes > kWave || (o.group_lanes & (o.group_lanes - 1)))
@@ -79,19 +80,29 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     // need no realignment (the paper's applicability rule, end of Section 3.2.1).
     const bool whole_lines = (row_bytes % line == 0) && (table_addr % (uintptr_t)line == 0);
     variant = (row_bytes < line || whole_lines) ? ZCG_VARIANT_ROWVEC : ZCG_VARIANT_ALIGNED;
-    // Long unaligned rows over the host link: one half-line read per ~8+ lines is a net gain
-    // (measured +2...4 % on 1,032...2,408-byte rows with 8- or 16-byte lanes); on short rows
-    // it is a loss, with 4-byte lanes it is neutral.
+    // Unaligned rows of more than a line over the host link: row ends that fit half a line go
+    // through 64-byte scalar reads. From 1 KiB on every such end does (measured +2...4 % on
+    // 1,032...2,408-byte rows with 8- or 16-byte lanes: one more request per 8+ lines, 64 bytes
+    // less); on shorter rows only ends whose line would be requested alone anyway, which saves
+    // bytes without adding requests (measured +1.5...4 % on 160...800-byte rows, config 2's
+    // 400-byte rows among them; converting every end there loses 6 %).
     // A short list of long rows is split over several wavefronts per row (below), which the
     // half-line kernel does not do: filling the link matters more there than 64 bytes per row.
     const bool will_split = o.row_splits ? o.row_splits > 1
                                          : (n_idx < 2048 && row_bytes >= (int64_t)8 * kWave * vec_cap * unroll);
-    if (variant == ZCG_VARIANT_ALIGNED && host_resident && row_bytes >= 1024 && !will_split &&
+    if (variant == ZCG_VARIANT_ALIGNED && host_resident && row_bytes > 128 && !will_split &&
         (w >= 8 || (w >= 4 && vec_cap >= 8 && o.shifted_stores != 2)))
       variant = ZCG_VARIANT_HALFLINE, line = 128;
   }
 
+  // The half-line kernels wait for their scalar reads row by row, so they want a wavefront per
+  // row rather than a stride (measured on 400-byte rows: 45.6 GB/s with 2048 blocks, 46.4 with
+  // 16384 or more; no difference on 2,408-byte rows).
+  if (variant == ZCG_VARIANT_HALFLINE && host_resident && !o.max_blocks) max_blocks = 16384;
+
   plan->variant = variant;
+  plan->half_ends = variant != ZCG_VARIANT_HALFLINE ? 0
+                    : (o.half_ends ? o.half_ends : (row_bytes >= 1024 ? 1 : 2));
   plan->row_splits = 1;
   plan->line_bytes = line;
   plan->unroll = unroll;
