@@ -4,7 +4,8 @@ Measured behaviour (rocprofv3 counters, see the profiles): a vector load of mapp
 host memory costs every 128-byte line it touches, whole; a wave-uniform load
 through the scalar data cache costs one 64-byte half line. The model counts,
 per row, the lines its byte range spans (and for the half-line kernel the ends
-that are fetched as half lines). Lines shared by different rows of one list are
+that are fetched as half lines), and the requests these make when lines of one
+256-byte aligned pair travel together. Lines shared by different rows of one list are
 counted once per row: the hardware saves a little more when such rows are
 processed close together.
 """
@@ -22,21 +23,50 @@ def row_spans(row_bytes: int, idx: np.ndarray, base_addr: int = 0):
     return start, start + row_bytes
 
 
-def link_bytes_per_row(row_bytes: int, idx: np.ndarray, base_addr: int = 0,
-                       halfline: bool = False) -> float:
-    """Mean bytes fetched over the link per listed row."""
+def _split(row_bytes: int, idx: np.ndarray, base_addr: int, half_ends: int):
+    """Per row: lines left to vector loads (first, last, count) and which ends go through the
+    scalar path. half_ends: 0 none, 1 every end that fits half a line, 2 only ends whose line
+    would be requested alone (its partner in the 256-byte aligned pair is not part of the row)."""
     s, e = row_spans(row_bytes, idx, base_addr)
     first_line = s // LINE
     last_line = (e - 1) // LINE
-    lines = last_line - first_line + 1
-    total = lines * LINE
-    if halfline:
+    head = np.zeros(s.shape, dtype=bool)
+    tail = np.zeros(s.shape, dtype=bool)
+    vs = s.copy()
+    if half_ends:
+        next_line = (first_line + 1) * LINE
         head = (s % LINE) >= HALF  # the row starts in the upper half of its first line
-        after_head = np.where(head, np.minimum(e, (first_line + 1) * LINE), s)
-        tail = (after_head < e) & (((e - 1) % LINE) < HALF)  # and ends in a lower half
-        total = total - HALF * head.astype(np.int64) - HALF * tail.astype(np.int64)
+        if half_ends == 2:
+            head &= ((first_line % 2) == 1) | (e <= next_line)
+        vs = np.where(head, np.minimum(e, next_line), s)
+        tail = (vs < e) & (((e - 1) % LINE) < HALF)  # and ends in a lower half
+        if half_ends == 2:
+            tail &= ((last_line % 2) == 0) | (vs >= last_line * LINE)
+    ve = np.where(tail, np.maximum(vs, last_line * LINE), e)
+    return s, e, vs, ve, head, tail
+
+
+def link_bytes_per_row(row_bytes: int, idx: np.ndarray, base_addr: int = 0,
+                       halfline: bool = False, half_ends: int = 0) -> float:
+    """Mean bytes fetched over the link per listed row (``halfline=True`` is ``half_ends=1``)."""
+    half_ends = half_ends or (1 if halfline else 0)
+    s, e, vs, ve, head, tail = _split(row_bytes, idx, base_addr, half_ends)
+    lines = np.where(ve > vs, (ve - 1) // LINE - vs // LINE + 1, 0)
+    total = lines * LINE + HALF * head.astype(np.int64) + HALF * tail.astype(np.int64)
     return float(np.mean(total))
 
 
-def useful_fraction(row_bytes: int, idx: np.ndarray, base_addr: int = 0, halfline: bool = False) -> float:
-    return row_bytes / link_bytes_per_row(row_bytes, idx, base_addr, halfline)
+def link_requests_per_row(row_bytes: int, idx: np.ndarray, base_addr: int = 0,
+                          half_ends: int = 0) -> float:
+    """Mean read requests per listed row as the link sees them. Inferred from timing, not from a
+    counter: two lines of one 256-byte aligned pair asked for together travel as one request,
+    a lone line is one request, a 64-byte scalar read is one request, and the link serves about
+    320 M requests/s whatever their size (up to its byte rate)."""
+    s, e, vs, ve, head, tail = _split(row_bytes, idx, base_addr, half_ends)
+    pairs = np.where(ve > vs, (ve - 1) // (2 * LINE) - vs // (2 * LINE) + 1, 0)
+    return float(np.mean(pairs + head.astype(np.int64) + tail.astype(np.int64)))
+
+
+def useful_fraction(row_bytes: int, idx: np.ndarray, base_addr: int = 0, halfline: bool = False,
+                    half_ends: int = 0) -> float:
+    return row_bytes / link_bytes_per_row(row_bytes, idx, base_addr, halfline, half_ends)

@@ -103,6 +103,10 @@ def test_launch_knobs_do_not_change_the_result(dim, dtype):
             # one block only: the grid-stride loop does all the work
             o = z.LaunchOpts(variant=variant, max_blocks=1)
             assert_same_bits(run_gather(table, idx, dtype, o), want, "max_blocks=1")
+            for half_ends in (1, 2):  # which row ends the half-line kernel takes through 64-byte reads
+                for unroll in (1, 4):
+                    o = z.LaunchOpts(variant=variant, half_ends=half_ends, unroll=unroll, max_blocks=64)
+                    assert_same_bits(run_gather(table, idx, dtype, o), want, f"half_ends{half_ends} u{unroll}")
             # several wavefronts per row (rows wider than one wave pass; else the knob is moot)
             for splits, unroll, vec in ((2, 1, 0), (3, 2, 0), (7, 1, 4), (64, 1, 2), (4096, 1, 1)):
                 if vec and vec < table.elem_bytes:
@@ -365,7 +369,9 @@ def test_seeded_random_shapes_knobs_and_offsets():
                                 group_lanes=int(rng.choice([0, 1, 8, 64])),
                                 shifted_stores=int(rng.integers(0, 3)), nt_loads=int(rng.integers(0, 4)),
                                 nt_stores=int(rng.integers(0, 3)),
-                                max_blocks=int(rng.choice([0, 1, 7, 300])))
+                                max_blocks=int(rng.choice([0, 1, 7, 300])),
+                                row_splits=int(rng.choice([0, 1, 2, 5])),
+                                half_ends=int(rng.integers(0, 3)))
             what = f"case {ci}: {dtype} dim={dim} rows={n_rows} n_idx={n_idx} t_off={t_off} o_off={o_off} " \
                    f"opts={[getattr(opts, f) for f, _ in opts._fields_]}"
             if rng.random() < 0.4 and opts.variant != z.VARIANT_NAIVE:

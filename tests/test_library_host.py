@@ -162,7 +162,7 @@ def test_plan_picks_width_group_and_variant():
     p = plan(100, "f32", n_idx=3)
     assert p["blocks"] == 1
     for bad in (dict(unroll=3), dict(line_bytes=48), dict(vec_bytes=2), dict(vec_bytes=3), dict(variant=5),
-                dict(nt_loads=4), dict(shifted_stores=3), dict(row_splits=-1), dict(row_splits=4097)):
+                dict(nt_loads=4), dict(shifted_stores=3), dict(row_splits=-1), dict(row_splits=4097), dict(half_ends=3)):
         with pytest.raises(z.ZcgError):
             plan(100, "f32", **bad)
 
@@ -177,6 +177,14 @@ def test_plan_splits_long_rows_of_short_lists():
     assert plan(602, "f32", n_idx=4, row_splits=2, unroll=1)["row_splits"] == 2
     assert plan(100, "f32", n_idx=4, row_splits=8)["row_splits"] == 1  # one pass covers the row
     assert plan(16384, "f32", n_idx=16, variant=z.VARIANT_HALFLINE, row_splits=8)["row_splits"] == 1
+
+
+def test_plan_half_line_policy():
+    assert plan(100, "f32")["half_ends"] == 0  # not a half-line kernel
+    assert plan(100, "f32", variant=z.VARIANT_HALFLINE)["half_ends"] == 2  # short rows: lone ends only
+    assert plan(602, "f32", variant=z.VARIANT_HALFLINE)["half_ends"] == 1  # 1 KiB and more: every end
+    assert plan(100, "f32", variant=z.VARIANT_HALFLINE, half_ends=1)["half_ends"] == 1
+    assert plan(602, "f32", variant=z.VARIANT_HALFLINE, half_ends=2)["half_ends"] == 2
 
 
 def covered_bytes(row_bytes, src_addr, p):

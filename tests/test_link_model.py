@@ -15,28 +15,38 @@ def measured_table():
     """(config, kernel) -> link bytes per row from profiles/gather_variants_cfg2_cfg3.txt."""
     out = {}
     for line in open(os.path.join(ROOT, "profiles", "gather_variants_cfg2_cfg3.txt")):
-        m = re.match(r"\s+(cfg\d)\s+(\w+)\s+[\d.]+\s+[\d.]+ \([\d.]+\)\s+([\d.]+)", line)
+        m = re.match(r"\s+(cfg\d)\s+([\w-]+)\s+[\d.]+\s+[\d.]+ \([\d.]+\)\s+([\d.]+)\s+([\d.]+)\s+([\d.]+)", line)
         if m:
-            out[(m.group(1), m.group(2))] = float(m.group(3))
+            out[(m.group(1), m.group(2))] = (float(m.group(3)), float(m.group(4)), float(m.group(5)))
     return out
 
 
 def test_model_matches_measured_link_bytes():
     meas = measured_table()
-    assert len(meas) == 8
+    assert len(meas) == 10
     for k in (2, 3):
         cfg = wl.config(k)
         idx = wl.index_lists(cfg)[0]
         whole = link_model.link_bytes_per_row(cfg.row_bytes, idx)
-        half = link_model.link_bytes_per_row(cfg.row_bytes, idx, halfline=True)
         # rows processed close together share a few lines, so the chip moves slightly less
         for name in ("rowvec", "aligned"):
-            got = meas[(f"cfg{k}", name)]
+            got = meas[(f"cfg{k}", name)][0]
             assert whole * 0.99 <= got <= whole * 1.001, (k, name, whole, got)
-        got = meas[(f"cfg{k}", "halfline")]
-        assert half * 0.99 <= got <= half * 1.001, (k, half, got)
+        for name, policy in (("half-all", 1), ("half-lone", 2)):
+            want = link_model.link_bytes_per_row(cfg.row_bytes, idx, half_ends=policy)
+            got, _, reads64 = meas[(f"cfg{k}", name)]
+            assert want * 0.99 <= got <= want * 1.001, (k, name, want, got)
+            # the 64-byte reads the counters saw are the row ends the model sends that way
+            ends = (whole - want) / 64.0
+            assert abs(reads64 - ends) < 0.02, (k, name, reads64, ends)
         # the naive mapping re-requests lines straddled by two load instructions: always more
-        assert meas[(f"cfg{k}", "naive")] > whole * 1.05
+        assert meas[(f"cfg{k}", "naive")][0] > whole * 1.05
+    # the default benchmark command's own counter file agrees with the lone-end policy
+    text = open(os.path.join(ROOT, "profiles", "gather_cfg2_counters.txt")).read()
+    per_row = float(re.search(r"^link_read_bytes_per_row = ([\d.]+)", text, re.M).group(1))
+    cfg = wl.config(2)
+    want = link_model.link_bytes_per_row(cfg.row_bytes, wl.index_lists(cfg)[0], half_ends=2)
+    assert want * 0.99 <= per_row <= want * 1.001
 
 
 def test_closed_forms():
@@ -52,3 +62,15 @@ def test_closed_forms():
     assert link_model.link_bytes_per_row(32, idx) == 128.0
     assert link_model.link_bytes_per_row(32, idx, halfline=True) == 64.0
     assert abs(link_model.useful_fraction(400, idx) - 0.78125) < 1e-12
+    # lone ends only: half of the 400-byte rows start on the upper line of a pair, and of those
+    # half start in its upper half, half end in the lower half of a lower line -> 32 bytes saved
+    assert link_model.link_bytes_per_row(400, idx, half_ends=2) == 480.0
+    assert link_model.link_bytes_per_row(32, idx, half_ends=2) == 64.0  # a row inside half a line is alone
+    # requests: pairs of lines, lone lines and 64-byte reads count one each
+    assert link_model.link_requests_per_row(400, idx) == 2.5
+    assert link_model.link_requests_per_row(400, idx, half_ends=1) == 3.0
+    assert link_model.link_requests_per_row(400, idx, half_ends=2) == 2.5
+    assert link_model.link_requests_per_row(512, idx) == 2.0
+    assert link_model.link_requests_per_row(512, idx, base_addr=128) == 3.0
+    assert link_model.link_requests_per_row(256, idx, base_addr=128) == 2.0
+    assert link_model.link_requests_per_row(128, idx) == 1.0
