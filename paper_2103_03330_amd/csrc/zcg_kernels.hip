@@ -326,19 +326,31 @@ __device__ __forceinline__ RowSplit split_row(uint64_t S, uint64_t row_bytes, bo
   return p;
 }
 
-// Moves the head / tail pieces of one row (wave-uniform S, r). Lanes 0-15 carry
-// the head piece's 16 dwords, lanes 16-31 the tail piece's.
-__device__ __forceinline__ void move_pieces(const RowSplit& sp, uint64_t S, uint64_t row_bytes,
-                                            uint8_t* __restrict__ out_row, unsigned wave_lane) {
+// The head / tail pieces of one row (wave-uniform S, r) travel as two 64-byte scalar reads;
+// lanes 0-15 then store the head piece's 16 dwords, lanes 16-31 the tail piece's. Loading and
+// storing are separate steps so that a kernel can issue its vector loads in between: the wave
+// then waits for one round trip per row, not two.
+struct RowPieces {
+  u32x16 hv, tv;
+};
+
+__device__ __forceinline__ RowPieces load_pieces(const RowSplit& sp) {
   const uint64_t dummy = (uint64_t)(uintptr_t)zcg_dummy_chunk;
-  const u32x16 hv = *(half_line_ptr)(sp.has_head ? sp.head_addr : dummy);
-  const u32x16 tv = *(half_line_ptr)(sp.has_tail ? sp.tail_addr : dummy);
+  RowPieces q;
+  q.hv = *(half_line_ptr)(sp.has_head ? sp.head_addr : dummy);
+  q.tv = *(half_line_ptr)(sp.has_tail ? sp.tail_addr : dummy);
+  return q;
+}
+
+__device__ __forceinline__ void store_pieces(const RowSplit& sp, const RowPieces& q, uint64_t S,
+                                             uint64_t row_bytes, uint8_t* __restrict__ out_row,
+                                             unsigned wave_lane) {
   const unsigned k = wave_lane & 15u;
   uint32_t h = 0, t = 0;
 #pragma unroll
   for (unsigned j = 0; j < 16; ++j) {
-    h = (k == j) ? hv[j] : h;
-    t = (k == j) ? tv[j] : t;
+    h = (k == j) ? q.hv[j] : h;
+    t = (k == j) ? q.tv[j] : t;
   }
   const bool is_head_lane = wave_lane < 16u;
   const uint64_t a = (is_head_lane ? sp.head_addr : sp.tail_addr) + 4u * k;  // source of my dword
@@ -346,6 +358,12 @@ __device__ __forceinline__ void move_pieces(const RowSplit& sp, uint64_t S, uint
   const uint64_t hi = is_head_lane ? sp.vs : S + row_bytes;
   const bool mine = wave_lane < 32u && (is_head_lane ? sp.has_head : sp.has_tail) && a >= lo && a < hi;
   if (mine) *reinterpret_cast<uint32_t*>(out_row + (a - S)) = is_head_lane ? h : t;
+}
+
+__device__ __forceinline__ void move_pieces(const RowSplit& sp, uint64_t S, uint64_t row_bytes,
+                                            uint8_t* __restrict__ out_row, unsigned wave_lane) {
+  const RowPieces q = load_pieces(sp);
+  store_pieces(sp, q, S, row_bytes, out_row, wave_lane);
 }
 
 template <int W, int WS, int U, bool NTS>
@@ -422,11 +440,17 @@ zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restric
   constexpr int64_t kStep = (int64_t)kWave * W;
   const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
 
+  // the next row's index is fetched while the current row is in flight
+  int64_t row_next = wave < n_idx ? idx[wave] : 0;
   for (int64_t r = wave; r < n_idx; r += n_waves) {
-    const uint64_t S = uniform_u64((uint64_t)(uintptr_t)(table + idx[r] * row_bytes), 0);
+    const int64_t row = row_next;
+    const int64_t r_next = r + n_waves;
+    row_next = idx[r_next < n_idx ? r_next : r];
+    const uint64_t S = uniform_u64((uint64_t)(uintptr_t)(table + row * row_bytes), 0);
     const RowSplit sp = split_row(S, (uint64_t)row_bytes, only_lone != 0);
     uint8_t* out_row = out + r * row_bytes;
-    if (sp.has_head || sp.has_tail) move_pieces(sp, S, (uint64_t)row_bytes, out_row, lane);
+    bool pieces_pending = sp.has_head || sp.has_tail;  // wave-uniform
+    const RowPieces q = load_pieces(sp);               // issued now, used after the vector loads
     const uint64_t a0 = (sp.vs & ~(uint64_t)127u) + (uint64_t)lane * W;  // line-aligned lane mapping
     for (uint64_t a = a0; a < sp.ve; a += kStep * U) {
       vec v[U];
@@ -437,12 +461,19 @@ zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restric
         ok[u] = (au + W > sp.vs) && (au < sp.ve);
         v[u] = load_chunk<W, 0>(ok[u] ? table + (au - (uint64_t)(uintptr_t)table) : dummy);
       }
+      if (pieces_pending) {
+        store_pieces(sp, q, S, (uint64_t)row_bytes, out_row, lane);
+        pieces_pending = false;
+      }
 #pragma unroll
       for (int u = 0; u < U; ++u)
         if (ok[u])
           store_shifted<W, WS, NTS>(out_row, (int64_t)(a + (uint64_t)u * kStep - S),
                                     (int64_t)(sp.vs - S), (int64_t)(sp.ve - S), v[u]);
     }
+    // lanes whose first chunk lies beyond the vector part never entered the loop (all lanes,
+    // when the two pieces are the whole row): every lane passes one of the two calls once
+    if (pieces_pending) store_pieces(sp, q, S, (uint64_t)row_bytes, out_row, lane);
   }
 }
 
