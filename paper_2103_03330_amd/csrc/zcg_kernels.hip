@@ -282,6 +282,8 @@ zcg_k_rows_wide_shift(const uint8_t* __restrict__ table, const int64_t* __restri
 // A 400-byte row then moves 3 lines + 1 half line (448 bytes) instead of 4
 // lines (512 bytes). This is the paper's aim (Section 3.2.1: as few and as full
 // link requests as possible for unaligned rows) with this chip's own means.
+// A scalar read is a link request of its own, so it pays only where the line it
+// replaces would have been a request of its own too (see split_row).
 // Requires 4-byte-aligned rows, table and output. The scalar cache is
 // invalidated at kernel start like the other caches, never written.
 // ---------------------------------------------------------------------------
