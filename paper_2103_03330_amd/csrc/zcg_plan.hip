@@ -84,8 +84,8 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     // through 64-byte scalar reads. From 1 KiB on every such end does (measured +2...4 % on
     // 1,032...2,408-byte rows with 8- or 16-byte lanes: one more request per 8+ lines, 64 bytes
     // less); on shorter rows only ends whose line would be requested alone anyway, which saves
-    // bytes without adding requests (measured +1.5...4 % on 160...800-byte rows, config 2's
-    // 400-byte rows among them; converting every end there loses 6 %).
+    // bytes without adding requests (measured +1.5...4 % on 160...800-byte rows, +6 % on
+    // sampled minibatches of 400-byte rows; converting every end there loses 6 %).
     // A short list of long rows is split over several wavefronts per row (below), which the
     // half-line kernel does not do: filling the link matters more there than 64 bytes per row.
     const bool will_split = o.row_splits ? o.row_splits > 1
