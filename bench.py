@@ -554,6 +554,31 @@ def run_request_blocks(args, z, wl, np, torch):
                         "rows_per_s": round(n_idx / t * 1e3)})
             print(f"# {pts[-1]}", file=sys.stderr, flush=True)
             view.close()
+        if rb == 256:
+            # the same rows fetched one 128-byte line per load instruction (64 lanes x 2 bytes), with
+            # one or two such loads in flight: do the two lines of a pair have to share an instruction?
+            view = z.table_from_device(base.device_ptr, n_rows, rb, "i8")
+            out8 = out.view(torch.int8).view(n_idx, rb)
+            for in_flight in (1, 2):
+                o = z.LaunchOpts(variant=z.VARIANT_ROWVEC, unroll=in_flight, nt_loads=2, max_blocks=8192,
+                                 vec_bytes=2, group_lanes=64)
+                for _ in range(3):
+                    z.gather_ex(view, idx, out8, o, stream=cur)
+                torch.cuda.synchronize()
+                ms = []
+                for _ in range(20):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(cur)
+                    z.gather_ex(view, idx, out8, o, stream=cur)
+                    e1.record(cur)
+                    e1.synchronize()
+                    ms.append(e0.elapsed_time(e1))
+                t = float(np.median(ms))
+                pts.append({"row_bytes": rb, "base_offset": 0, "gbps": round(n_idx * rb / t / 1e6, 2),
+                            "rows_per_s": round(n_idx / t * 1e3),
+                            "loads": f"one line per instruction, {in_flight} in flight per wave"})
+                print(f"# {pts[-1]}", file=sys.stderr, flush=True)
+            view.close()
         base.close()
     return pts
 
