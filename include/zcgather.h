@@ -84,7 +84,8 @@ typedef struct zcg_launch_opts {
   int variant;     /* ZCG_VARIANT_*                                                   */
   int max_blocks;  /* cap on the grid size (blocks of 256 lanes); the kernels stride   */
   int unroll;      /* independent loads in flight per lane: 1, 2, 4 or 8               */
-  int line_bytes;  /* alignment target of ALIGNED: 32, 64, 128 or 256                  */
+  int line_bytes;  /* alignment target of ALIGNED: 32, 64, 128 or 256 (default 128; 256
+                      for host-resident rows that take several wave passes)            */
   int nt_loads;    /* 1: non-temporal table loads, 2: plain loads, 3: system scope;
                       default: plain for host tables, non-temporal for HBM tables      */
   int nt_stores;   /* 1: non-temporal output stores, 2: plain stores                   */

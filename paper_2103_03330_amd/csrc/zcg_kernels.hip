@@ -453,7 +453,9 @@ zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restric
     uint8_t* out_row = out + r * row_bytes;
     bool pieces_pending = sp.has_head || sp.has_tail;  // wave-uniform
     const RowPieces q = load_pieces(sp);               // issued now, used after the vector loads
-    const uint64_t a0 = (sp.vs & ~(uint64_t)127u) + (uint64_t)lane * W;  // line-aligned lane mapping
+    // passes start on a 256-byte pair boundary, so that the two lines of a pair are always
+    // requested by the same batch of loads and travel as one request
+    const uint64_t a0 = (sp.vs & ~(uint64_t)255u) + (uint64_t)lane * W;
     for (uint64_t a = a0; a < sp.ve; a += kStep * U) {
       vec v[U];
       bool ok[U];

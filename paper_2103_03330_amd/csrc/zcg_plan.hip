@@ -127,8 +127,8 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
       wl = vec_cap;
     plan->vec_bytes = wl;
     plan->store_bytes = w;
-    const int64_t worst_span = row_bytes + (line_mapped ? line - w : 0);
-    const int64_t chunks = (worst_span + wl - 1) / wl;
+    int64_t worst_span = row_bytes + (line_mapped ? line - w : 0);
+    int64_t chunks = (worst_span + wl - 1) / wl;
     int lg = 0;
     while (lg < 6 && ((int64_t)1 << lg) < chunks) ++lg;
     if (lg < min_lg) lg = min_lg;
@@ -139,6 +139,17 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
       want_blocks = ((groups << lg) + kBlock - 1) / kBlock;
     } else {
       plan->log2_group = 6;
+      // Rows that take several passes anyway: over the host link the passes start on a 256-byte
+      // boundary, so that the two lines of a 256-byte aligned pair are always requested by the
+      // same batch of loads and travel as one request (measured +1...2 % on 1,028...2,408-byte
+      // rows; the half-line kernel does the same on its own).
+      if (variant == ZCG_VARIANT_ALIGNED && host_resident && !o.line_bytes && line < 256) {
+        line = 256;
+        plan->line_bytes = line;
+        worst_span = row_bytes + line - w;
+        chunks = (worst_span + wl - 1) / wl;
+        plan->iters = (int)((chunks + kWave - 1) / kWave);
+      }
       // One wavefront per row keeps only unroll * 64 * vec_bytes bytes of that row in flight
       // (measured: 0.7 GB/s per row over the host link), so a short list of long rows cannot
       // fill the link. Then several wavefronts share a row, each taking a contiguous piece of
