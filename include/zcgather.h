@@ -60,7 +60,8 @@ extern "C" {
 /* ---- gather kernels (zcg_gather_variant / zcg_gather_ex) --------------- */
 #define ZCG_VARIANT_AUTO 0    /* rows shorter than a line or made of whole lines: ROWVEC;
                                  else ALIGNED, or HALFLINE for host-resident rows of more
-                                 than a line with at least 4-byte granularity           */
+                                 than a line with at least 4-byte granularity (also for
+                                 multi-pass whole-line rows off the 256-byte pair grid)  */
 #define ZCG_VARIANT_NAIVE 1   /* one element per lane over the flat output, no alignment
                                  care: the paper's baseline kernel (Section 4.1.2 (c))  */
 #define ZCG_VARIANT_ROWVEC 2  /* a lane group per row, widest vector, loads start at the

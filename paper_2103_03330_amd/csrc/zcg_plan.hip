@@ -79,7 +79,13 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     // Rows shorter than a line, or made of whole lines on a line-aligned base,
     // need no realignment (the paper's applicability rule, end of Section 3.2.1).
     const bool whole_lines = (row_bytes % line == 0) && (table_addr % (uintptr_t)line == 0);
-    variant = (row_bytes < line || whole_lines) ? ZCG_VARIANT_ROWVEC : ZCG_VARIANT_ALIGNED;
+    // Over the host link whole-line rows that take several passes and do not sit on the 256-byte
+    // pair grid (640, 896, 1152 ... bytes) still gain 0.7...1.4 % from passes that start on pair
+    // boundaries, which the line-mapped kernels provide.
+    const bool off_pair_grid = host_resident && row_bytes > (int64_t)kWave * vec_cap &&
+                               (row_bytes % 256 != 0 || table_addr % 256 != 0);
+    variant = (row_bytes < line || (whole_lines && !off_pair_grid)) ? ZCG_VARIANT_ROWVEC
+                                                                    : ZCG_VARIANT_ALIGNED;
     // Unaligned rows of more than a line over the host link: row ends that fit half a line go
     // through 64-byte scalar reads. From 1 KiB on every such end does (measured +2...4 % on
     // 1,032...2,408-byte rows with 8- or 16-byte lanes: one more request per 8+ lines, 64 bytes
