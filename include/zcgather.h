@@ -214,7 +214,7 @@ int zcg_gather_ex(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, voi
  * 128-byte rows, sort included it still wins below ~128 bytes per row).
  *   order_dev : device, n_idx int64, a permutation of [0, n_idx); entries outside
  *               that range are undefined behaviour
- * NAIVE has no ordered form (ZCG_EINVAL); HALFLINE is run as ALIGNED.
+ * NAIVE has no ordered form (ZCG_EINVAL).
  */
 int zcg_gather_ordered(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,
                        int64_t n_idx, void* out_dev, void* stream, const zcg_launch_opts* opts);

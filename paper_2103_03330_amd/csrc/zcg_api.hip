@@ -214,16 +214,7 @@ static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64
   zcg_plan plan;
   int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, host_resident, opts, &plan);
   if (rc) return rc;
-  if (order_dev) {
-    if (plan.variant == ZCG_VARIANT_NAIVE) return ZCG_EINVAL;
-    if (plan.variant == ZCG_VARIANT_HALFLINE) {  // no ordered form: take the plain aligned kernel
-      zcg_launch_opts o = {};
-      if (opts) o = *opts;
-      o.variant = ZCG_VARIANT_ALIGNED;
-      rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, host_resident, &o, &plan);
-      if (rc) return rc;
-    }
-  }
+  if (order_dev && plan.variant == ZCG_VARIANT_NAIVE) return ZCG_EINVAL;
   hipError_t e = zcg_launch_gather(plan, t->dev, idx_dev, order_dev, n_idx, out_dev, t->row_bytes,
                                    t->elem, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);

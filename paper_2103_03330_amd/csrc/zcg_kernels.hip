@@ -371,8 +371,8 @@ __device__ __forceinline__ void move_pieces(const RowSplit& sp, uint64_t S, uint
 template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
-                       int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int log2_g,
-                       int only_lone) {
+                       const int64_t* __restrict__ order, int64_t n_idx, uint8_t* __restrict__ out,
+                       int64_t row_bytes, int log2_g, int only_lone) {
   typedef typename vec_of<W>::type vec;
   const unsigned wave_lane = threadIdx.x & (kWave - 1);
   const unsigned lane = threadIdx.x & ((1u << log2_g) - 1u);
@@ -386,14 +386,18 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
   // wave-uniform trip count: the wave's first group decides
   for (int64_t wbase = wave_group0; wbase < n_idx; wbase += n_groups * U) {
     int64_t row_id[U];
+    int64_t out_row[U];  // position in the list = output row
     uint64_t src[U];
     vec v[U];
     bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t r = wbase + my_group + (int64_t)u * n_groups;
-      row_id[u] = idx[r < n_idx ? r : n_idx - 1];
+      const int64_t k = wbase + my_group + (int64_t)u * n_groups;
+      const int64_t kc = k < n_idx ? k : n_idx - 1;
+      out_row[u] = order ? order[kc] : kc;
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u) row_id[u] = idx[out_row[u]];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int64_t r = wbase + my_group + (int64_t)u * n_groups;
@@ -412,19 +416,19 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
         const int64_t r = wbase + g + (int64_t)u * n_groups;  // uniform
         if (r < n_idx) {
           const uint64_t S = uniform_u64(src[u], g << log2_g);
+          const int64_t dst = (int64_t)uniform_u64((uint64_t)out_row[u], g << log2_g);
           const RowSplit sp = split_row(S, (uint64_t)row_bytes, only_lone != 0);
           if (sp.has_head || sp.has_tail)
-            move_pieces(sp, S, (uint64_t)row_bytes, out + r * row_bytes, wave_lane);
+            move_pieces(sp, S, (uint64_t)row_bytes, out + dst * row_bytes, wave_lane);
         }
       }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       if (ok[u]) {
-        const int64_t r = wbase + my_group + (int64_t)u * n_groups;
         const RowSplit sp = split_row(src[u], (uint64_t)row_bytes, only_lone != 0);
         const int64_t off = (int64_t)((src[u] & ~(uint64_t)127u) + (uint64_t)lane_off - src[u]);
-        store_shifted<W, WS, NTS>(out + r * row_bytes, off, (int64_t)(sp.vs - src[u]),
+        store_shifted<W, WS, NTS>(out + out_row[u] * row_bytes, off, (int64_t)(sp.vs - src[u]),
                                   (int64_t)(sp.ve - src[u]), v[u]);
       }
     }
@@ -434,7 +438,8 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
 template <int W, int WS, int U, bool NTS>
 __global__ void __launch_bounds__(kBlock)
 zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restrict__ idx,
-                     int64_t n_idx, uint8_t* __restrict__ out, int64_t row_bytes, int only_lone) {
+                     const int64_t* __restrict__ order, int64_t n_idx, uint8_t* __restrict__ out,
+                     int64_t row_bytes, int only_lone) {
   typedef typename vec_of<W>::type vec;
   const unsigned lane = threadIdx.x & (kWave - 1);
   const int64_t n_waves = ((int64_t)gridDim.x * kBlock) / kWave;
@@ -443,11 +448,16 @@ zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restric
   const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
 
   // the next row's index is fetched while the current row is in flight
-  int64_t row_next = wave < n_idx ? idx[wave] : 0;
-  for (int64_t r = wave; r < n_idx; r += n_waves) {
-    const int64_t row = row_next;
-    const int64_t r_next = r + n_waves;
-    row_next = idx[r_next < n_idx ? r_next : r];
+  int64_t r_next = 0, row_next = 0;  // output row (position in the list) and table row
+  if (wave < n_idx) {
+    r_next = order ? order[wave] : wave;
+    row_next = idx[r_next];
+  }
+  for (int64_t k = wave; k < n_idx; k += n_waves) {
+    const int64_t r = r_next, row = row_next;
+    const int64_t k_next = k + n_waves < n_idx ? k + n_waves : k;
+    r_next = order ? order[k_next] : k_next;
+    row_next = idx[r_next];
     const uint64_t S = uniform_u64((uint64_t)(uintptr_t)(table + row * row_bytes), 0);
     const RowSplit sp = split_row(S, (uint64_t)row_bytes, only_lone != 0);
     uint8_t* out_row = out + r * row_bytes;
@@ -577,16 +587,16 @@ hipError_t launch_rows(const zcg_plan& p, const uint8_t* table, const int64_t* i
     if (p.variant == ZCG_VARIANT_HALFLINE) {
       if (p.iters == 1) {
         if (p.nt_stores)
-          zcg_k_rows_narrow_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+          zcg_k_rows_narrow_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                      row_bytes, p.log2_group, lone);
         else
-          zcg_k_rows_narrow_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+          zcg_k_rows_narrow_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                       row_bytes, p.log2_group, lone);
       } else {
         if (p.nt_stores)
-          zcg_k_rows_wide_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes, lone);
+          zcg_k_rows_wide_half<W, W, U, true><<<grid, block, 0, s>>>(table, idx, order, n_idx, out, row_bytes, lone);
         else
-          zcg_k_rows_wide_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out, row_bytes, lone);
+          zcg_k_rows_wide_half<W, W, U, false><<<grid, block, 0, s>>>(table, idx, order, n_idx, out, row_bytes, lone);
       }
       return hipGetLastError();
     }
@@ -636,17 +646,17 @@ hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* 
     if (p.variant == ZCG_VARIANT_HALFLINE) {
       if (p.iters == 1) {
         if (p.nt_stores)
-          zcg_k_rows_narrow_half<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+          zcg_k_rows_narrow_half<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                          row_bytes, p.log2_group, lone);
         else
-          zcg_k_rows_narrow_half<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+          zcg_k_rows_narrow_half<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                           row_bytes, p.log2_group, lone);
       } else {
         if (p.nt_stores)
-          zcg_k_rows_wide_half<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+          zcg_k_rows_wide_half<W, WS, U, true><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                        row_bytes, lone);
         else
-          zcg_k_rows_wide_half<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, n_idx, out,
+          zcg_k_rows_wide_half<W, WS, U, false><<<grid, block, 0, s>>>(table, idx, order, n_idx, out,
                                                                         row_bytes, lone);
       }
       return hipGetLastError();
@@ -711,9 +721,8 @@ hipError_t launch_flat(const zcg_plan& p, const void* table, const int64_t* idx,
 hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t* idx,
                              const int64_t* order, int64_t n_idx, void* out, int64_t row_bytes,
                              int elem, hipStream_t stream) {
-  // a processing order exists only for the row kernels that start at or below the row start
-  if (order && (p.variant == ZCG_VARIANT_NAIVE || p.variant == ZCG_VARIANT_HALFLINE))
-    return hipErrorInvalidValue;
+  // the flat kernel has no processing order
+  if (order && p.variant == ZCG_VARIANT_NAIVE) return hipErrorInvalidValue;
   if (p.variant == ZCG_VARIANT_NAIVE) {
     const int64_t dim = row_bytes / elem;
     switch (elem) {
