@@ -60,8 +60,8 @@ extern "C" {
 /* ---- gather kernels (zcg_gather_variant / zcg_gather_ex) --------------- */
 #define ZCG_VARIANT_AUTO 0    /* rows shorter than a line or made of whole lines: ROWVEC;
                                  else ALIGNED, or HALFLINE for host-resident rows of more
-                                 than a line with at least 4-byte granularity (also for
-                                 multi-pass whole-line rows off the 256-byte pair grid)  */
+                                 than a line (also for multi-pass whole-line rows off
+                                 the 256-byte pair grid)                                */
 #define ZCG_VARIANT_NAIVE 1   /* one element per lane over the flat output, no alignment
                                  care: the paper's baseline kernel (Section 4.1.2 (c))  */
 #define ZCG_VARIANT_ROWVEC 2  /* a lane group per row, widest vector, loads start at the
@@ -75,7 +75,9 @@ extern "C" {
                                   fetched as 64-byte reads through the scalar data cache:
                                   on gfx950 a vector load of host memory always costs the
                                   whole 128-byte line on the link, a scalar load half of
-                                  it. Needs 4-byte-aligned rows and bases, else ALIGNED. */
+                                  it. Needs loads of 4 bytes or more (vec_bytes >= 8 with
+                                  shifted stores when rows or bases are only 1- or 2-byte
+                                  granular), else ALIGNED.                              */
 #define ZCG_VARIANT_COUNT 5
 
 typedef struct zcg_table zcg_table; /* opaque */

@@ -284,7 +284,7 @@ zcg_k_rows_wide_shift(const uint8_t* __restrict__ table, const int64_t* __restri
 // link requests as possible for unaligned rows) with this chip's own means.
 // A scalar read is a link request of its own, so it pays only where the line it
 // replaces would have been a request of its own too (see split_row).
-// Requires 4-byte-aligned rows, table and output. The scalar cache is
+// Rows, table and output of any granularity (1- and 2-byte elements are stored one by one). The scalar cache is
 // invalidated at kernel start like the other caches, never written.
 // ---------------------------------------------------------------------------
 typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
@@ -344,6 +344,9 @@ __device__ __forceinline__ RowPieces load_pieces(const RowSplit& sp) {
   return q;
 }
 
+// WS = granularity of rows and bases (the stores' alignment): dwords when it is 4 or more,
+// else the dword's 1- or 2-byte elements one by one.
+template <int WS>
 __device__ __forceinline__ void store_pieces(const RowSplit& sp, const RowPieces& q, uint64_t S,
                                              uint64_t row_bytes, uint8_t* __restrict__ out_row,
                                              unsigned wave_lane) {
@@ -358,14 +361,26 @@ __device__ __forceinline__ void store_pieces(const RowSplit& sp, const RowPieces
   const uint64_t a = (is_head_lane ? sp.head_addr : sp.tail_addr) + 4u * k;  // source of my dword
   const uint64_t lo = is_head_lane ? S : sp.ve;
   const uint64_t hi = is_head_lane ? sp.vs : S + row_bytes;
-  const bool mine = wave_lane < 32u && (is_head_lane ? sp.has_head : sp.has_tail) && a >= lo && a < hi;
-  if (mine) *reinterpret_cast<uint32_t*>(out_row + (a - S)) = is_head_lane ? h : t;
+  const bool has = wave_lane < 32u && (is_head_lane ? sp.has_head : sp.has_tail);
+  const uint32_t val = is_head_lane ? h : t;
+  if constexpr (WS >= 4) {
+    if (has && a >= lo && a < hi) *reinterpret_cast<uint32_t*>(out_row + (a - S)) = val;
+  } else {
+    typedef typename vec_of<WS>::type elem_t;
+#pragma unroll
+    for (int j = 0; j < 4 / WS; ++j) {
+      const uint64_t aj = a + (uint64_t)(j * WS);
+      if (has && aj >= lo && aj < hi)
+        *reinterpret_cast<elem_t*>(out_row + (aj - S)) = (elem_t)(val >> (8 * j * WS));
+    }
+  }
 }
 
+template <int WS>
 __device__ __forceinline__ void move_pieces(const RowSplit& sp, uint64_t S, uint64_t row_bytes,
                                             uint8_t* __restrict__ out_row, unsigned wave_lane) {
   const RowPieces q = load_pieces(sp);
-  store_pieces(sp, q, S, row_bytes, out_row, wave_lane);
+  store_pieces<WS>(sp, q, S, row_bytes, out_row, wave_lane);
 }
 
 template <int W, int WS, int U, bool NTS>
@@ -419,7 +434,7 @@ zcg_k_rows_narrow_half(const uint8_t* __restrict__ table, const int64_t* __restr
           const int64_t dst = (int64_t)uniform_u64((uint64_t)out_row[u], g << log2_g);
           const RowSplit sp = split_row(S, (uint64_t)row_bytes, only_lone != 0);
           if (sp.has_head || sp.has_tail)
-            move_pieces(sp, S, (uint64_t)row_bytes, out + dst * row_bytes, wave_lane);
+            move_pieces<WS>(sp, S, (uint64_t)row_bytes, out + dst * row_bytes, wave_lane);
         }
       }
     }
@@ -476,7 +491,7 @@ zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restric
         v[u] = load_chunk<W, 0>(ok[u] ? table + (au - (uint64_t)(uintptr_t)table) : dummy);
       }
       if (pieces_pending) {
-        store_pieces(sp, q, S, (uint64_t)row_bytes, out_row, lane);
+        store_pieces<WS>(sp, q, S, (uint64_t)row_bytes, out_row, lane);
         pieces_pending = false;
       }
 #pragma unroll
@@ -487,7 +502,7 @@ zcg_k_rows_wide_half(const uint8_t* __restrict__ table, const int64_t* __restric
     }
     // lanes whose first chunk lies beyond the vector part never entered the loop (all lanes,
     // when the two pieces are the whole row): every lane passes one of the two calls once
-    if (pieces_pending) store_pieces(sp, q, S, (uint64_t)row_bytes, out_row, lane);
+    if (pieces_pending) store_pieces<WS>(sp, q, S, (uint64_t)row_bytes, out_row, lane);
   }
 }
 
@@ -642,7 +657,7 @@ hipError_t launch_shift(const zcg_plan& p, const uint8_t* table, const int64_t* 
   const int64_t splits = p.row_splits > 1 ? p.row_splits : 1;
   const int64_t piece = piece_bytes_of(p, row_bytes, W, U);
   const int lone = p.half_ends == 2 ? 1 : 0;
-  if constexpr (WS >= 4) {
+  {
     if (p.variant == ZCG_VARIANT_HALFLINE) {
       if (p.iters == 1) {
         if (p.nt_stores)

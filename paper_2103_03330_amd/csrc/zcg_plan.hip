@@ -71,8 +71,9 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   w = floor_pow2_divisor((uint64_t)table_addr, w);
   w = floor_pow2_divisor((uint64_t)out_addr, w);
 
-  // HALFLINE moves dwords through the scalar path: needs 4-byte granularity everywhere.
-  const bool half_ok = (w >= 4);
+  // HALFLINE moves dwords through the scalar path and needs loads of at least 4 bytes: rows and
+  // bases 4-byte granular, or less with wide line-aligned loads and element-wise (shifted) stores.
+  const bool half_ok = (w >= 4) || (vec_cap >= 8 && o.shifted_stores != 2);
   if (variant == ZCG_VARIANT_HALFLINE && !half_ok) variant = ZCG_VARIANT_ALIGNED;
   if (variant == ZCG_VARIANT_HALFLINE) line = 128;
   if (variant == ZCG_VARIANT_AUTO) {
@@ -97,7 +98,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     const bool will_split = o.row_splits ? o.row_splits > 1
                                          : (n_idx < 2048 && row_bytes >= (int64_t)8 * kWave * vec_cap * unroll);
     if (variant == ZCG_VARIANT_ALIGNED && host_resident && row_bytes > 128 && !will_split &&
-        (w >= 8 || (w >= 4 && vec_cap >= 8 && o.shifted_stores != 2)))
+        (w >= 8 || (vec_cap >= 8 && o.shifted_stores != 2)))
       variant = ZCG_VARIANT_HALFLINE, line = 128;
   }
 

@@ -128,7 +128,9 @@ def test_plan_picks_width_group_and_variant():
     t_host_like = z.plan_gather(t, 1000, 0x7E0000000000, z.LaunchOpts(variant=z.VARIANT_HALFLINE))
     t.close()
     assert (t_host_like["variant"], t_host_like["log2_group"]) == (z.VARIANT_HALFLINE, 5)
-    p = plan(99, "f16", variant=z.VARIANT_HALFLINE)  # 198-byte rows: no 4-byte granularity
+    p = plan(99, "f16", variant=z.VARIANT_HALFLINE)  # 198-byte rows: 2-byte granular, wide loads
+    assert (p["variant"], p["vec_bytes"], p["store_bytes"]) == (z.VARIANT_HALFLINE, 16, 2)
+    p = plan(99, "f16", variant=z.VARIANT_HALFLINE, shifted_stores=2)  # 2-byte loads: no scalar path
     assert p["variant"] == z.VARIANT_ALIGNED
     p = plan(602, "f32")  # 2,408-byte rows: 8-byte lanes, a wave per row, several passes
     assert (p["variant"], p["vec_bytes"], p["store_bytes"], p["log2_group"]) == (z.VARIANT_ALIGNED, 16, 8, 6)
