@@ -315,7 +315,9 @@ int zcg_synthetic_compute(void* stream, int blocks, int64_t iters, float* sink_d
  *   gather_stream : stream the list copies and gathers run on (e.g. one from
  *                   zcg_stream_create_cu_mask); NULL = the pipeline creates its own
  * The pipeline owns, per buffer, a pinned staging area and a device copy of the
- * index list (max_rows int64 each). Threads: ONE producer thread (submit,
+ * index list (max_rows int64 each). For host-resident tables with rows of at
+ * most 128 bytes it also owns the memory of zcg_make_order and gathers every
+ * list in ascending table order (same result, fewer link requests). Threads: ONE producer thread (submit,
  * submit_wait, finish) and ONE consumer thread (next, acquire, release) may run
  * at the same time; they may also be the same thread. The consumer takes slot
  * numbers either from submit's result or from zcg_pipeline_next, not from both.

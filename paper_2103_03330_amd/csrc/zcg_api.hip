@@ -196,7 +196,7 @@ int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
                     const zcg_launch_opts* opts, zcg_plan* plan) {
   if (!zcg_is_live(t)) return ZCG_EHANDLE;
   return zcg_make_plan(t->row_bytes, t->elem, (uintptr_t)t->dev, (uintptr_t)out_dev, n_idx,
-                       t->kind != ZCG_KIND_DEVICE, opts, plan);
+                       t->kind != ZCG_KIND_DEVICE, false, opts, plan);
 }
 
 static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,
@@ -212,7 +212,8 @@ static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64
   if (o0 < t1 && t0 < o1) return ZCG_EALIAS;
   const bool host_resident = t->kind != ZCG_KIND_DEVICE;
   zcg_plan plan;
-  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, host_resident, opts, &plan);
+  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, host_resident, order_dev != nullptr, opts,
+                         &plan);
   if (rc) return rc;
   if (order_dev && plan.variant == ZCG_VARIANT_NAIVE) return ZCG_EINVAL;
   hipError_t e = zcg_launch_gather(plan, t->dev, idx_dev, order_dev, n_idx, out_dev, t->row_bytes,

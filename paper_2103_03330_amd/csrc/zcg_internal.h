@@ -27,7 +27,8 @@ int zcg_fail_hip(hipError_t e);  // records e for zcg_last_hip_error, returns ZC
 
 // zcg_kernels.hip
 int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t out_addr,
-                  int64_t n_idx, bool host_resident, const zcg_launch_opts* opts, zcg_plan* plan);
+                  int64_t n_idx, bool host_resident, bool ordered, const zcg_launch_opts* opts,
+                  zcg_plan* plan);  // ordered: the rows will be walked in ascending table order
 hipError_t zcg_launch_gather(const zcg_plan& plan, const void* table, const int64_t* idx,
                              const int64_t* order, int64_t n_idx, void* out, int64_t row_bytes, int elem,
                              hipStream_t stream);

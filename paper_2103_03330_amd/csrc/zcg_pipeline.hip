@@ -24,6 +24,12 @@ struct zcg_pipeline {
   int64_t max_rows = 0;
   int n_buffers = 0;
   bool own_stream = false;
+  // Rows of at most one line over the host link are bound by the request rate; walked in
+  // ascending table order, neighbouring rows share lines and pairs of lines (measured +12 %
+  // on 128-byte rows, +30 % on 32-byte rows, sort included). The pipeline owns the memory
+  // the sort needs, so it does this by itself.
+  bool sorts = false;
+  int64_t sort_ws_bytes = 0;
   hipStream_t gather_stream = nullptr;
   // A buffer goes FREE -> FILLING (producer is enqueuing into it) -> READY (its
   // gather is enqueued and `gathered` recorded) -> FREE again on release.
@@ -32,6 +38,8 @@ struct zcg_pipeline {
     void* out = nullptr;            // caller-owned
     int64_t* idx_dev = nullptr;     // library-owned
     int64_t* idx_pinned = nullptr;  // library-owned
+    int64_t* order = nullptr;       // library-owned, only when the pipeline sorts (see `sorts`)
+    void* sort_ws = nullptr;        // library-owned workspace of the sort
     hipEvent_t gathered = nullptr;  // recorded on the gather stream after the gather
     hipEvent_t released = nullptr;  // recorded on the consumer stream by release()
     State state = FREE;
@@ -58,6 +66,8 @@ void free_slots(zcg_pipeline* p) {
     if (s.released) (void)hipEventDestroy(s.released);
     if (s.idx_dev) (void)hipFree(s.idx_dev);
     if (s.idx_pinned) (void)hipHostFree(s.idx_pinned);
+    if (s.order) (void)hipFree(s.order);
+    if (s.sort_ws) (void)hipFree(s.sort_ws);
   }
   if (p->own_stream && p->gather_stream) (void)hipStreamDestroy(p->gather_stream);
 }
@@ -118,7 +128,14 @@ int submit_impl(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx, int tim
     std::memcpy(s.idx_pinned, idx_host, (size_t)n_idx * sizeof(int64_t));
     e = hipMemcpyAsync(s.idx_dev, s.idx_pinned, (size_t)n_idx * sizeof(int64_t),
                        hipMemcpyHostToDevice, p->gather_stream);
-    if (e == hipSuccess) rc = zcg_gather(p->table, s.idx_dev, n_idx, s.out, p->gather_stream);
+    if (e == hipSuccess && p->sorts) {
+      rc = zcg_make_order(s.idx_dev, n_idx, p->table->n_rows, s.order, s.sort_ws, p->sort_ws_bytes,
+                          p->gather_stream);
+      if (rc == ZCG_OK)
+        rc = zcg_gather_ordered(p->table, s.idx_dev, s.order, n_idx, s.out, p->gather_stream, nullptr);
+    } else if (e == hipSuccess) {
+      rc = zcg_gather(p->table, s.idx_dev, n_idx, s.out, p->gather_stream);
+    }
   }
   // recorded even after a failure above when possible: whatever did get enqueued must be
   // covered by the event the next use of this slot waits for
@@ -166,6 +183,8 @@ int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, voi
   p->max_rows = max_rows;
   p->n_buffers = n_buffers;
   p->slots.resize((size_t)n_buffers);
+  p->sorts = t->kind != ZCG_KIND_DEVICE && t->row_bytes <= 128;
+  if (p->sorts && zcg_order_workspace_bytes(max_rows, &p->sort_ws_bytes) != ZCG_OK) p->sorts = false;
   hipError_t e = hipSuccess;
   if (gather_stream) {
     p->gather_stream = static_cast<hipStream_t>(gather_stream);
@@ -180,6 +199,9 @@ int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, voi
     if (e == hipSuccess)
       e = hipHostMalloc(reinterpret_cast<void**>(&s.idx_pinned), (size_t)max_rows * sizeof(int64_t),
                         hipHostMallocDefault);
+    if (e == hipSuccess && p->sorts)
+      e = hipMalloc(reinterpret_cast<void**>(&s.order), (size_t)max_rows * sizeof(int64_t));
+    if (e == hipSuccess && p->sorts) e = hipMalloc(&s.sort_ws, (size_t)p->sort_ws_bytes);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&s.gathered, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&s.released, hipEventDisableTiming);
   }

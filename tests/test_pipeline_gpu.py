@@ -178,3 +178,30 @@ def test_bounded_waits_time_out():
         torch.cuda.synchronize()
         pipe.close()
         table.close()
+
+
+def test_ring_sorts_short_rows_by_itself():
+    """Tables with rows of at most a line are gathered in ascending table order inside the ring;
+    the delivered rows are still in list order."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    torch.cuda.set_device(0)
+    for dim, dtype, tdt in ((16, "f16", torch.float16), (32, "f32", torch.float32), (5, "f32", torch.float32)):
+        n_rows = 200_000
+        table = z.alloc_table(n_rows, dim, dtype)
+        wl.fill_table_ptr(table.host_ptr, n_rows, dim, dtype, seed=47 + dim)
+        lists = [wl.uniform_indices(n, n_rows, seed=n) for n in (70_001, 1, 33_333, 70_001)]
+        bufs = [torch.zeros((70_001, dim), dtype=tdt, device="cuda") for _ in range(2)]
+        pipe = z.pipeline_create(table, 70_001, bufs)
+        try:
+            for idx in lists:
+                slot = pipe.submit(idx)
+                buf, n = pipe.acquire(slot)
+                torch.cuda.synchronize()
+                assert n == idx.size
+                assert buf[:n].cpu().numpy().tobytes() == oracle_gather(table.host_array(), idx).tobytes()
+                pipe.release(slot)
+        finally:
+            torch.cuda.synchronize()
+            pipe.close()
+            table.close()
