@@ -1,56 +1,59 @@
 """Access-pattern model of the paper's indexing kernel (TEST INFRASTRUCTURE ONLY).
 
-Follows the steps of the indexing kernel of Section 3.2.1 (Listing 2) in the
-paper's notation -- one thread per linear element ``i``, ``dstIdx = i / feat_size``,
-``offset = i % feat_size``, and, when enabled, the circular-shift stage that
-rotates each row's thread->element mapping by ``diff`` -- and counts the link
-read requests the way the section counts them: one request per distinct
-(warp, cache line) pair touched by a warp's loads.
+What Section 3.2.1 describes, stated as a map instead of a program: the kernel
+runs one thread per element of the dense output, threads numbered in output
+order, 32 consecutive threads forming a warp. Thread t belongs to output row
+r = t div F (F = elements per row) and has position p = t mod F in it. Without
+the alignment stage it copies element p of the row. With the stage, every row
+is *rotated*: the thread at position p copies element (p + rot_r) mod F, where
+rot_r = (first output element of row r - first source element of row r) mod 32.
+Lane k of a warp then always reads a source element whose index is congruent to
+k modulo 32, i.e. a warp's reads start on a line boundary of the source; the
+misalignment moves to the writes. The stage applies only to rows longer than a
+warp that are not a whole number of warps (the section's applicability rule).
 
-The paper prints one worked case (a 480-byte row, second row of the table):
-8 requests without the shift, 5 with it. ``tests/golden/`` holds it.
+Requests are counted as the section counts them: a warp's loads cost one link
+read per distinct source line they touch.
+
+The paper prints one worked case (a 480-byte row, the second row of the table):
+8 requests without the stage, 5 with it. ``tests/golden/`` holds it.
 """
 from __future__ import annotations
 
-from typing import List, Sequence, Tuple
+from typing import Sequence, Tuple
+
+import numpy as np
 
 
-def thread_offsets(i: int, feat_size: int, idx_list: Sequence[int], shift: bool,
-                   warp_size: int = 32) -> Tuple[int, int]:
-    """(dstOffset, srcOffset), in elements, handled by the thread with linear index ``i``."""
-    dstIdx = i // feat_size
-    offset = i % feat_size
-    dstStart = dstIdx * feat_size
-    srcStart = idx_list[dstIdx] * feat_size
-    dstOffset = offset + dstStart
-    srcOffset = offset + srcStart
-    # Applicability rule: rows shorter than a line, or a whole number of lines, are left alone.
-    if shift and feat_size > warp_size and feat_size % warp_size != 0:
-        diff = (dstStart - srcStart) % warp_size  # Python's % is already non-negative
-        dstOffset += diff
-        srcOffset += diff
-        if srcOffset >= srcStart + feat_size:  # wrapped past the row end: rotate back
-            dstOffset -= feat_size
-            srcOffset -= feat_size
-    return dstOffset, srcOffset
+def row_rotations(feat_size: int, idx_list: Sequence[int], shift: bool, warp_size: int = 32
+                  ) -> np.ndarray:
+    """rot_r for every output row (all zero when the stage is off or does not apply)."""
+    src_first = np.asarray(idx_list, dtype=np.int64) * feat_size
+    dst_first = np.arange(len(src_first), dtype=np.int64) * feat_size
+    if not shift or feat_size <= warp_size or feat_size % warp_size == 0:
+        return np.zeros_like(src_first)
+    return np.mod(dst_first - src_first, warp_size)
 
 
-def copy_pairs(feat_size: int, idx_list: Sequence[int], shift: bool, warp_size: int = 32
-               ) -> List[Tuple[int, int]]:
-    """All (dstOffset, srcOffset) pairs the kernel performs for this index list."""
-    n = len(idx_list) * feat_size
-    return [thread_offsets(i, feat_size, idx_list, shift, warp_size) for i in range(n)]
+def element_map(feat_size: int, idx_list: Sequence[int], shift: bool, warp_size: int = 32
+                ) -> Tuple[np.ndarray, np.ndarray]:
+    """(dst, src): for every thread, in thread order, the output element it writes and the
+    source element it reads (flat element indices)."""
+    src_first = np.asarray(idx_list, dtype=np.int64) * feat_size
+    rot = row_rotations(feat_size, idx_list, shift, warp_size)
+    t = np.arange(len(src_first) * feat_size, dtype=np.int64)
+    r, p = np.divmod(t, feat_size)
+    within = np.mod(p + rot[r], feat_size)  # the row's elements, rotated by rot_r
+    return r * feat_size + within, src_first[r] + within
 
 
 def count_read_requests(feat_size: int, idx_list: Sequence[int], shift: bool, warp_size: int = 32,
                         line_bytes: int = 128, elem_bytes: int = 4) -> int:
-    """Distinct (warp, source cache line) pairs over all loads of one kernel pass."""
-    seen = set()
-    n = len(idx_list) * feat_size
-    for i in range(n):
-        _, srcOffset = thread_offsets(i, feat_size, idx_list, shift, warp_size)
-        seen.add((i // warp_size, (srcOffset * elem_bytes) // line_bytes))
-    return len(seen)
+    """Distinct (warp, source line) pairs over all loads of one kernel pass."""
+    _, src = element_map(feat_size, idx_list, shift, warp_size)
+    warp = np.arange(src.size, dtype=np.int64) // warp_size
+    line = (src * elem_bytes) // line_bytes
+    return int(np.unique(np.stack([warp, line]), axis=1).shape[1])
 
 
 def outstanding_requests(bandwidth_bytes_per_s: float, request_bytes: float, rtt_s: float) -> float:
