@@ -271,11 +271,11 @@ def run_provisioning(args, z, wl, np, torch, link_peak):
     sink = torch.zeros(256, dtype=torch.float32, device="cuda")
     comp_blocks = n_cus * 64  # many short blocks: no tail when some compute units are masked off
     iters = 4000
-    z.synthetic_compute(cur, comp_blocks, iters, sink)
+    probe.synthetic_compute(cur, comp_blocks, iters, sink)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(5):
-        z.synthetic_compute(cur, comp_blocks, iters, sink)
+        probe.synthetic_compute(cur, comp_blocks, iters, sink)
     torch.cuda.synchronize()
     per = (time.perf_counter() - t0) / 5
     iters = max(1000, int(iters * 2.0e-3 / per))  # about 2 ms alone: twice one gather
@@ -286,16 +286,16 @@ def run_provisioning(args, z, wl, np, torch, link_peak):
         t = time.perf_counter()
         for i in range(reps):
             z.gather_ex(table, idx_dev[i % 16], outs[i & 1], None, n_idx=lists[i % 16].size, stream=gs)
-            z.synthetic_compute(cs if not same_stream else gs, comp_blocks, iters, sink)
+            probe.synthetic_compute(cs if not same_stream else gs, comp_blocks, iters, sink)
         gs.synchronize()
         cs.synchronize()
         return (time.perf_counter() - t) / reps * 1e3
 
-    z.synthetic_compute(cur, comp_blocks, iters, sink)
+    probe.synthetic_compute(cur, comp_blocks, iters, sink)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(reps):
-        z.synthetic_compute(cur, comp_blocks, iters, sink)
+        probe.synthetic_compute(cur, comp_blocks, iters, sink)
     torch.cuda.synchronize()
     compute_alone = (time.perf_counter() - t0) / reps * 1e3
     gather_alone = float(np.mean([a.size for a in lists])) * rb / gather_rate(cur) / 1e6
@@ -314,7 +314,7 @@ def run_provisioning(args, z, wl, np, torch, link_peak):
         mc.close()
         print(f"# {overlap[-1]}", file=sys.stderr, flush=True)
     table.close()
-    rtt_us = z.measure_host_read_latency(20000)
+    rtt_us = probe.measure_host_read_latency(20000)
     full = share_curve[-1]["gbps"]
     lines_per_s = full * 1e9 / rb * 4  # a 400-byte row costs four 128-byte lines
     littles = {"host_read_round_trip_us": round(rtt_us, 3),
@@ -349,7 +349,7 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
         a = pinned[i % 16]
         idx_dev[:a.numel()].copy_(a, non_blocking=True)
         z.gather(table, idx_dev, bufs[0], n_idx=a.numel(), stream=cur)
-        z.synthetic_compute(cur, comp_blocks, iters, sink)
+        probe.synthetic_compute(cur, comp_blocks, iters, sink)
         torch.cuda.synchronize()
 
     only = args.pipeline_mode  # run one mode only (for kernel-trace profiles)
@@ -377,7 +377,7 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
             slot = pipe.submit(lists[i % 16]) if i < reps else None  # producer runs one ahead
             if prev is not None:
                 pipe.acquire(prev, cons)
-                z.synthetic_compute(cons, comp_blocks, iters, sink)
+                probe.synthetic_compute(cons, comp_blocks, iters, sink)
                 pipe.release(prev, cons)
             prev = slot
         cons.synchronize()
@@ -410,7 +410,7 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
             t_s += time.perf_counter() - ts
             idx_big[:a.numel()].copy_(a, non_blocking=False)
             z.gather(table, idx_big, big, n_idx=a.numel(), stream=cur)
-            z.synthetic_compute(cur, comp_blocks, iters, sink)
+            probe.synthetic_compute(cur, comp_blocks, iters, sink)
             torch.cuda.synchronize()
         ms = (time.perf_counter() - t) / reps * 1e3
         g.close()
@@ -465,7 +465,7 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
                     if slot is None:
                         break
                     pipe.acquire(slot, cons)
-                    z.synthetic_compute(cons, comp_blocks, iters, sink)
+                    probe.synthetic_compute(cons, comp_blocks, iters, sink)
                     pipe.release(slot, cons)
                 cons.synchronize()
             except Exception as exc:  # noqa: BLE001
@@ -508,11 +508,11 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
         if only in ("all", f"mask{n}"):
             cases.append({"mode": f"pipeline, 2 buffers, gather on {n} CUs / compute on {n_cus - n}",
                           "ms_per_minibatch": round(pipelined(n), 3)})
-    z.synthetic_compute(cur, comp_blocks, iters, sink)
+    probe.synthetic_compute(cur, comp_blocks, iters, sink)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(reps):
-        z.synthetic_compute(cur, comp_blocks, iters, sink)
+        probe.synthetic_compute(cur, comp_blocks, iters, sink)
     torch.cuda.synchronize()
     compute_ms = (time.perf_counter() - t0) / reps * 1e3
     table.close()
@@ -661,6 +661,8 @@ def main():
 
     import paper_2103_03330_amd as z
     import zcg_workload as wl
+    global probe
+    from paper_2103_03330_amd import probe
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -670,7 +672,7 @@ def main():
     n_cores = wl.default_threads()
     n_batches = args.batches or (50 if args.config == 4 else 16)
 
-    link_peak = z.measure_h2d(1 << 30, 10)
+    link_peak = probe.measure_h2d(1 << 30, 10)
     nominal, link_name = nominal_link_gbps()
 
     if args.config == 5:
@@ -783,7 +785,7 @@ def main():
 
     # shader-issued ceiling: GPU lanes streaming consecutive bytes of mapped host memory into HBM
     # with the gather's access shape (a kernel of its own, so the gather's profile stays clean)
-    stream_gbps = z.measure_host_stream_read(256 << 20, 10)
+    stream_gbps = probe.measure_host_stream_read(256 << 20, 10)
     # the index list's own host-to-device copy (the paper sends it by DMA before the gather)
     pin_idx = torch.from_numpy(lists[0]).pin_memory()
     idx_h2d_us = event_ms(lambda: idx_dev[0].copy_(pin_idx, non_blocking=True)) * 1e3

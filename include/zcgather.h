@@ -61,7 +61,9 @@ extern "C" {
 #define ZCG_VARIANT_AUTO 0    /* rows shorter than a line or made of whole lines: ROWVEC;
                                  else ALIGNED, or HALFLINE for host-resident rows of more
                                  than a line (also for multi-pass whole-line rows off
-                                 the 256-byte pair grid)                                */
+                                 the 256-byte pair grid). With workspace lent through
+                                 zcg_launch_opts, long lists of host-resident rows of at
+                                 most a line are walked in ascending table order.       */
 #define ZCG_VARIANT_NAIVE 1   /* one element per lane over the flat output, no alignment
                                  care: the paper's baseline kernel (Section 4.1.2 (c))  */
 #define ZCG_VARIANT_ROWVEC 2  /* a lane group per row, widest vector, loads start at the
@@ -110,6 +112,18 @@ typedef struct zcg_launch_opts {
                       requested alone (its partner in the 256-byte aligned pair is not
                       part of the row), which never adds a link request. Default: 1 for
                       rows of 1 KiB and more, 2 for shorter rows.                       */
+  void* workspace_dev;     /* optional: device memory, CALLER-OWNED, 256-byte aligned, that
+                      the call may overwrite while it runs on its stream (free to reuse
+                      once the stream has passed the call; two calls that overlap in
+                      time need two workspaces). With variant AUTO and at least
+                      zcg_gather_workspace_bytes(n_idx) bytes, zcg_gather_ex walks long
+                      lists (131,072 entries or more) of host-resident rows of at most
+                      128 bytes in ascending table order: it builds the order in the
+                      workspace with a few kernels of its own on the same stream, then
+                      gathers through it. The result is the same bit for bit; rows that
+                      share a line or a 256-byte pair of lines then share a link
+                      request. Ignored where that does not pay or does not fit.       */
+  int64_t workspace_bytes; /* size of workspace_dev in bytes (0 with a null pointer)       */
 } zcg_launch_opts;
 
 /* How one gather call is laid out on the GPU; filled by zcg_plan_gather. */
@@ -157,6 +171,20 @@ int zcg_alloc_table(int64_t n_rows, int64_t dim, int dtype, unsigned flags, int 
  */
 int zcg_table_from_device(void* dev_ptr, int64_t n_rows, int64_t dim, int dtype, int device,
                           zcg_table** out);
+
+/*
+ * A slice of a live table as a table of its own: rows of `dim` elements of
+ * `dtype` starting `byte_offset` bytes into the parent's memory (Section 3.1: the
+ * unified tensor is made from an EXISTING buffer, whose address and alignment the
+ * library does not choose -- a sub-tensor of a larger pinned allocation, a table
+ * with a header in front of it). No memory is pinned or copied; the view reads
+ * through the parent's mapping and stays host-resident if the parent is. It must
+ * lie inside the parent (ZCG_EINVAL), start on an element boundary (ZCG_EALIGN),
+ * and is dead once the parent is unregistered (ZCG_EHANDLE from then on);
+ * unregister the view itself to free its handle.
+ */
+int zcg_table_view(const zcg_table* parent, int64_t byte_offset, int64_t n_rows, int64_t dim,
+                   int dtype, zcg_table** out);
 
 /* Accessors; return NULL / 0 for a handle that is not live. */
 void* zcg_table_device_ptr(const zcg_table* t); /* pointer kernels read the table through */
@@ -222,18 +250,25 @@ int zcg_gather_ordered(const zcg_table* t, const int64_t* idx_dev, const int64_t
                        int64_t n_idx, void* out_dev, void* stream, const zcg_launch_opts* opts);
 
 /*
- * Builds that order on the GPU: a stable radix sort of (idx[i], i) pairs by idx.
- * Asynchronous on `stream`; allocates nothing: all temporary memory is the
- * caller's workspace (device, 256-byte aligned, at least
- * zcg_order_workspace_bytes(n_idx) bytes, free to reuse once the stream has
- * passed the call). n_rows bounds the index values (only the bits below it are
- * sorted). Equal indices keep their list order.
- * Not meant for stream capture: the library sort may record memory-set
- * operations of its own. Build the order eagerly, capture zcg_gather_ordered.
+ * Builds that order on the GPU: a stable least-significant-digit radix sort of
+ * (idx[i], i) by idx, hand-written for wave64 (digits of up to 8 bits; per digit a
+ * count, a prefix and a scatter kernel; deterministic). Equal indices keep their
+ * list order. Asynchronous on `stream`; allocates nothing: all temporary memory is
+ * the caller's workspace (device, 256-byte aligned, at least
+ * zcg_order_workspace_bytes(n_idx) bytes = about 8 bytes per entry plus 0.3 MB,
+ * free to reuse once the stream has passed the call). order_dev itself is used as
+ * a second buffer while the order is built. n_rows bounds the index values: only
+ * the bits below it are sorted, so entries outside [0, n_rows) still yield a
+ * permutation, just not an ascending one. n_idx < 2^32 (ZCG_EINVAL beyond).
+ * Safe under stream capture: only kernel nodes are recorded.
  */
 int zcg_order_workspace_bytes(int64_t n_idx, int64_t* bytes);
 int zcg_make_order(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_t* order_dev,
                    void* workspace_dev, int64_t workspace_bytes, void* stream);
+
+/* Bytes of zcg_launch_opts.workspace_dev that let zcg_gather_ex order a list of n_idx
+ * entries by itself: the order (8 bytes per entry) plus zcg_order_workspace_bytes. */
+int zcg_gather_workspace_bytes(int64_t n_idx, int64_t* bytes);
 
 /*
  * Host-only: the launch shape zcg_gather_ex would use for this table, output
@@ -275,13 +310,6 @@ int zcg_cpu_gather_memcpy_chunked(const zcg_table* t, const int64_t* idx_host, i
                                   int64_t chunk_rows, void* stream);
 
 /*
- * Link-peak probe (the denominator of the metric): median over `reps` timed
- * pinned host-to-device hipMemcpyAsync copies of `bytes` bytes, after one
- * warm-up, in GB/s (1e9 bytes). SYNCHRONOUS; allocates and frees its buffers.
- */
-int zcg_measure_h2d(int64_t bytes, int reps, int device, double* gb_per_s);
-
-/*
  * Resource provisioning (Section 3.2.2: the gather needs only a small share of
  * the GPU to saturate the link, the rest stays free for compute kernels). The
  * paper caps the gather's share with a process-level service; here a stream is
@@ -296,14 +324,6 @@ int zcg_measure_h2d(int64_t bytes, int reps, int device, double* gb_per_s);
 int zcg_stream_create_cu_mask(int device, const uint32_t* mask_words, int n_words, void** stream);
 int zcg_stream_destroy(void* stream);
 int zcg_device_cu_count(int device, int* n_cus);
-
-/*
- * A stand-in for the training kernels the gather overlaps with (Section 3.2.2,
- * Section 4.3): `blocks` blocks of 256 lanes, each lane runs `iters` dependent
- * fused multiply-adds and adds its result into sink_dev[lane id mod 256]
- * (device, 256 floats, CALLER-OWNED). Pure ALU work, asynchronous on `stream`.
- */
-int zcg_synthetic_compute(void* stream, int blocks, int64_t iters, float* sink_dev);
 
 /*
  * Minibatch pipeline, producer side (Section 3.3: sampler -> producer -> consumer
@@ -358,25 +378,6 @@ int zcg_pipeline_release(zcg_pipeline* p, int slot, void* consumer_stream);
 /* Waits for the gather stream, frees what the pipeline owns (never the output buffers).
  * No other thread may still be inside a call on p. */
 int zcg_pipeline_destroy(zcg_pipeline* p);
-
-/*
- * Round-trip time of one read of mapped host memory from a GPU lane: a single
- * lane follows `hops` (16 .. 2^22) dependent loads through a random cycle laid
- * over a 256 MiB mapped buffer, one slot per page. With the measured request
- * rate this gives the number of reads in flight (Little's law, the sizing
- * argument of Section 3.2.2). SYNCHRONOUS; allocates and frees its buffers.
- */
-int zcg_measure_host_read_latency(int device, int64_t hops, double* microseconds);
-
-/*
- * The rate at which GPU lanes themselves can pull consecutive bytes of mapped
- * host memory into HBM (the ceiling of any zero-copy gather): median over
- * `reps` runs of a plain streaming kernel with the gather's access shape over a
- * fresh mapped buffer of `bytes` bytes (a multiple of 4096), in GB/s (1e9
- * bytes). Compare with zcg_measure_h2d, the copy engine's rate over the same
- * link. SYNCHRONOUS; allocates and frees its buffers.
- */
-int zcg_measure_host_stream_read(int device, int64_t bytes, int reps, double* gb_per_s);
 
 /* Pinned host scratch for callers without another allocator (staging buffers). */
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr);

@@ -10,10 +10,10 @@ from .binding import (  # noqa: F401
     EBUSY, ECLOSED, ETIMEDOUT,
     ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER, ALLOC_UNCACHED, B8, B64, F16, F32, VARIANT_ALIGNED, VARIANT_AUTO, VARIANT_HALFLINE,
     VARIANT_NAIVE, VARIANT_NAMES, VARIANT_ROWVEC, LaunchOpts, MaskedStream, Pipeline, Table, ZcgError,
-    alloc_table, device_cu_count, stream_create_cu_mask, stream_destroy, synthetic_compute,
+    alloc_table, device_cu_count, stream_create_cu_mask, stream_destroy, table_view,
     cpu_gather_memcpy, cpu_gather_memcpy_chunked, gather, gather_ex, gather_ordered, gather_variant,
-    make_order, order_workspace_bytes,
-    last_hip_error, load_library, measure_h2d, measure_host_read_latency, measure_host_stream_read, pipeline_create, pinned_alloc, pinned_free, plan_gather,
+    make_order, order_workspace_bytes, gather_workspace_bytes,
+    last_hip_error, load_library, pipeline_create, pinned_alloc, pinned_free, plan_gather,
     register_table, strerror, table_from_device, unregister_table, validate_indices, version,
 )
 from .unified import UnifiedTensor, to_unified  # noqa: F401,E402

@@ -35,12 +35,12 @@ EXPORTS = [
     "zcg_table_from_device", "zcg_table_device_ptr", "zcg_table_host_ptr", "zcg_table_row_bytes",
     "zcg_table_n_rows", "zcg_unregister_table", "zcg_gather", "zcg_gather_variant",
     "zcg_gather_ex", "zcg_plan_gather", "zcg_validate_indices", "zcg_cpu_gather_memcpy",
-    "zcg_cpu_gather_memcpy_chunked", "zcg_measure_h2d", "zcg_pinned_alloc", "zcg_pinned_free",
+    "zcg_cpu_gather_memcpy_chunked", "zcg_pinned_alloc", "zcg_pinned_free",
     "zcg_version", "zcg_stream_create_cu_mask", "zcg_stream_destroy", "zcg_device_cu_count",
-    "zcg_synthetic_compute", "zcg_pipeline_create", "zcg_pipeline_submit", "zcg_pipeline_submit_wait",
+    "zcg_pipeline_create", "zcg_pipeline_submit", "zcg_pipeline_submit_wait",
     "zcg_pipeline_finish", "zcg_pipeline_next", "zcg_pipeline_acquire",
     "zcg_pipeline_release", "zcg_pipeline_destroy", "zcg_gather_ordered",
-    "zcg_order_workspace_bytes", "zcg_make_order", "zcg_measure_host_read_latency", "zcg_measure_host_stream_read",
+    "zcg_order_workspace_bytes", "zcg_make_order", "zcg_table_view", "zcg_gather_workspace_bytes",
 ]
 
 
@@ -50,7 +50,8 @@ class LaunchOpts(ctypes.Structure):
                 ("line_bytes", ctypes.c_int), ("nt_loads", ctypes.c_int),
                 ("nt_stores", ctypes.c_int), ("vec_bytes", ctypes.c_int),
                 ("group_lanes", ctypes.c_int), ("shifted_stores", ctypes.c_int),
-                ("row_splits", ctypes.c_int), ("half_ends", ctypes.c_int)]
+                ("row_splits", ctypes.c_int), ("half_ends", ctypes.c_int),
+                ("workspace_dev", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64)]
 
 
 class Plan(ctypes.Structure):
@@ -107,13 +108,11 @@ def load_library() -> ctypes.CDLL:
         "zcg_validate_indices": (i32, [vp, vp, i64, vp, ctypes.POINTER(i64)]),
         "zcg_cpu_gather_memcpy": (i32, [vp, vp, i64, vp, vp, i32, vp]),
         "zcg_cpu_gather_memcpy_chunked": (i32, [vp, vp, i64, vp, vp, i32, i64, vp]),
-        "zcg_measure_h2d": (i32, [i64, i32, i32, ctypes.POINTER(ctypes.c_double)]),
         "zcg_pinned_alloc": (i32, [i64, pvp]),
         "zcg_pinned_free": (i32, [vp]),
         "zcg_stream_create_cu_mask": (i32, [i32, ctypes.POINTER(ctypes.c_uint32), i32, pvp]),
         "zcg_stream_destroy": (i32, [vp]),
         "zcg_device_cu_count": (i32, [i32, ctypes.POINTER(i32)]),
-        "zcg_synthetic_compute": (i32, [vp, i32, i64, vp]),
         "zcg_pipeline_create": (i32, [vp, i64, i32, ctypes.POINTER(ctypes.c_void_p), vp, pvp]),
         "zcg_pipeline_submit": (i32, [vp, vp, i64, ctypes.POINTER(i32)]),
         "zcg_pipeline_submit_wait": (i32, [vp, vp, i64, i32, ctypes.POINTER(i32)]),
@@ -125,8 +124,8 @@ def load_library() -> ctypes.CDLL:
         "zcg_gather_ordered": (i32, [vp, vp, vp, i64, vp, vp, ctypes.POINTER(LaunchOpts)]),
         "zcg_order_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
         "zcg_make_order": (i32, [vp, i64, i64, vp, vp, i64, vp]),
-        "zcg_measure_host_read_latency": (i32, [i32, i64, ctypes.POINTER(ctypes.c_double)]),
-        "zcg_measure_host_stream_read": (i32, [i32, i64, i32, ctypes.POINTER(ctypes.c_double)]),
+        "zcg_table_view": (i32, [vp, i64, i64, i64, i32, pvp]),
+        "zcg_gather_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -260,6 +259,14 @@ def table_from_device(dev, n_rows: int, dim: int, dtype, device: int = 0) -> Tab
     return _new_table(rc, "zcg_table_from_device", out, n_rows, dim, dt)
 
 
+def table_view(parent: Table, byte_offset: int, n_rows: int, dim: int, dtype) -> Table:
+    """A slice of a live table as a table of its own (no pinning, no copy)."""
+    dt = _DTYPES.get(dtype, dtype)
+    out = ctypes.c_void_p()
+    rc = load_library().zcg_table_view(parent.handle, byte_offset, n_rows, dim, dt, ctypes.byref(out))
+    return _new_table(rc, "zcg_table_view", out, n_rows, dim, dt)
+
+
 def unregister_table(table: Table) -> None:
     table.close()
 
@@ -331,13 +338,6 @@ def cpu_gather_memcpy_chunked(table: Table, idx_host, staging_pinned, out_dev, c
     _check(rc, "zcg_cpu_gather_memcpy_chunked")
 
 
-def measure_h2d(n_bytes: int, reps: int = 10, device: int = 0) -> float:
-    """Median pinned host-to-device copy bandwidth in GB/s (1e9 bytes)."""
-    g = ctypes.c_double(0.0)
-    _check(load_library().zcg_measure_h2d(n_bytes, reps, device, ctypes.byref(g)), "zcg_measure_h2d")
-    return float(g.value)
-
-
 def pinned_alloc(n_bytes: int) -> int:
     p = ctypes.c_void_p()
     _check(load_library().zcg_pinned_alloc(n_bytes, ctypes.byref(p)), "zcg_pinned_alloc")
@@ -381,11 +381,6 @@ def stream_create_cu_mask(cu_ids, device: int = 0) -> MaskedStream:
 
 def stream_destroy(stream: MaskedStream) -> None:
     stream.close()
-
-
-def synthetic_compute(stream, blocks: int, iters: int, sink_dev) -> None:
-    _check(load_library().zcg_synthetic_compute(_stream(stream), blocks, iters, _ptr(sink_dev)),
-           "zcg_synthetic_compute")
 
 
 class Pipeline:
@@ -466,25 +461,15 @@ def order_workspace_bytes(n_idx: int) -> int:
     return int(b.value)
 
 
+def gather_workspace_bytes(n_idx: int) -> int:
+    b = ctypes.c_int64(0)
+    _check(load_library().zcg_gather_workspace_bytes(n_idx, ctypes.byref(b)), "zcg_gather_workspace_bytes")
+    return int(b.value)
+
+
 def make_order(idx_dev, n_rows: int, order_dev, workspace_dev, workspace_bytes: int,
                n_idx: Optional[int] = None, stream=None) -> None:
     _check_idx_tensor(idx_dev)
     rc = load_library().zcg_make_order(_ptr(idx_dev), _n_idx(idx_dev, n_idx), n_rows, _ptr(order_dev),
                                        _ptr(workspace_dev), workspace_bytes, _stream(stream))
     _check(rc, "zcg_make_order")
-
-
-def measure_host_read_latency(hops: int = 20000, device: int = 0) -> float:
-    """Round-trip time in microseconds of one dependent read of mapped host memory."""
-    us = ctypes.c_double(0.0)
-    _check(load_library().zcg_measure_host_read_latency(device, hops, ctypes.byref(us)),
-           "zcg_measure_host_read_latency")
-    return float(us.value)
-
-
-def measure_host_stream_read(n_bytes: int = 256 << 20, reps: int = 10, device: int = 0) -> float:
-    """GB/s at which GPU lanes stream consecutive bytes of mapped host memory into HBM."""
-    g = ctypes.c_double(0.0)
-    _check(load_library().zcg_measure_host_stream_read(device, n_bytes, reps, ctypes.byref(g)),
-           "zcg_measure_host_stream_read")
-    return float(g.value)

@@ -1,13 +1,12 @@
 // C-ABI entry points of libzcgather: table handles, the gather dispatch, the
-// index check and the link-peak probe. Kernels live in zcg_kernels.hip, the
-// CPU-gather baseline in zcg_cpu_baseline.hip.
+// index check and CU-masked streams. Kernels live in zcg_kernels.hip, the launch
+// planning in zcg_plan.hip, the order builder in zcg_order.hip, the CPU-gather
+// baseline in zcg_cpu_baseline.hip, the pipeline in zcg_pipeline.hip.
 #include <hip/hip_runtime.h>
 
-#include <algorithm>
 #include <mutex>
 #include <new>
 #include <unordered_set>
-#include <vector>
 
 #include "zcg_internal.h"
 
@@ -36,10 +35,12 @@ int check_shape(int64_t n_rows, int64_t dim, int dtype, zcg_table** out, int* el
 }
 
 zcg_table* make_handle(int kind, int dtype, int elem, int device, void* host, void* dev,
-                       int64_t n_rows, int64_t dim) {
+                       int64_t n_rows, int64_t dim, const zcg_table* parent = nullptr) {
   zcg_table* t = new (std::nothrow) zcg_table;
   if (!t) return nullptr;
   t->kind = kind; t->dtype = dtype; t->elem = elem; t->device = device;
+  t->parent = parent;
+  t->host_resident = parent ? parent->host_resident : kind != ZCG_KIND_DEVICE;
   t->host = host; t->dev = dev; t->n_rows = n_rows; t->dim = dim;
   t->row_bytes = dim * elem;
   std::lock_guard<std::mutex> lk(g_mu);
@@ -66,7 +67,9 @@ struct DeviceScope {
 bool zcg_is_live(const zcg_table* t) {
   if (!t) return false;
   std::lock_guard<std::mutex> lk(g_mu);
-  return g_live.count(t) != 0;
+  if (g_live.count(t) == 0) return false;
+  // a view lives only as long as the table it slices
+  return t->kind != ZCG_KIND_VIEW || g_live.count(t->parent) != 0;
 }
 
 int zcg_fail_hip(hipError_t e) {
@@ -77,7 +80,7 @@ int zcg_fail_hip(hipError_t e) {
 
 extern "C" {
 
-const char* zcg_version(void) { return "0.1"; }
+const char* zcg_version(void) { return "0.2"; }
 
 const char* zcg_strerror(int status) {
   switch (status) {
@@ -170,6 +173,27 @@ int zcg_table_from_device(void* dev_ptr, int64_t n_rows, int64_t dim, int dtype,
   return ZCG_OK;
 }
 
+int zcg_table_view(const zcg_table* parent, int64_t byte_offset, int64_t n_rows, int64_t dim,
+                   int dtype, zcg_table** out) {
+  int elem;
+  int rc = check_shape(n_rows, dim, dtype, out, &elem);
+  if (rc) return rc;
+  if (!zcg_is_live(parent)) return ZCG_EHANDLE;
+  if (byte_offset < 0) return ZCG_EINVAL;
+  const int64_t parent_bytes = parent->n_rows * parent->row_bytes;
+  const int64_t bytes = n_rows * dim * elem;
+  if (byte_offset > parent_bytes || bytes > parent_bytes - byte_offset) return ZCG_EINVAL;
+  char* dev = static_cast<char*>(parent->dev) + byte_offset;
+  if ((uintptr_t)dev % (uintptr_t)elem) return ZCG_EALIGN;
+  void* host = parent->host ? static_cast<char*>(parent->host) + byte_offset : nullptr;
+  // a view of a view hangs off the same root, so that liveness is one look-up
+  const zcg_table* root = parent->kind == ZCG_KIND_VIEW ? parent->parent : parent;
+  zcg_table* t = make_handle(ZCG_KIND_VIEW, dtype, elem, parent->device, host, dev, n_rows, dim, root);
+  if (!t) return ZCG_ENOMEM;
+  *out = t;
+  return ZCG_OK;
+}
+
 void* zcg_table_device_ptr(const zcg_table* t) { return zcg_is_live(t) ? t->dev : nullptr; }
 void* zcg_table_host_ptr(const zcg_table* t) { return zcg_is_live(t) ? t->host : nullptr; }
 int64_t zcg_table_row_bytes(const zcg_table* t) { return zcg_is_live(t) ? t->row_bytes : 0; }
@@ -196,13 +220,28 @@ int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
                     const zcg_launch_opts* opts, zcg_plan* plan) {
   if (!zcg_is_live(t)) return ZCG_EHANDLE;
   return zcg_make_plan(t->row_bytes, t->elem, (uintptr_t)t->dev, (uintptr_t)out_dev, n_idx,
-                       t->kind != ZCG_KIND_DEVICE, false, opts, plan);
+                       t->host_resident, false, opts, plan);
+}
+
+// Rows of at most one line over the host link are bound by the link's request rate; walked in
+// ascending table order, rows that share a line or a 256-byte pair of lines share a request
+// (measured with the order built on the clock: +25 % on 32-byte rows, +5...12 % on 64- and
+// 128-byte rows from ~128 k list entries on). A caller that lends workspace gets this from AUTO.
+static bool wants_order(const zcg_table* t, int64_t n_idx, const zcg_launch_opts* opts) {
+  if (!opts || !opts->workspace_dev || opts->variant != ZCG_VARIANT_AUTO) return false;
+  if (!t->host_resident || t->row_bytes > 128 || n_idx < 131072 || n_idx > (int64_t)UINT32_MAX)
+    return false;
+  if ((uintptr_t)opts->workspace_dev % 256) return false;
+  const int64_t order_bytes = (n_idx * 8 + 255) / 256 * 256;
+  return opts->workspace_bytes >= order_bytes + zcg_order_scratch_bytes(n_idx);
 }
 
 static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,
                          int64_t n_idx, void* out_dev, void* stream, const zcg_launch_opts* opts) {
   if (!zcg_is_live(t)) return ZCG_EHANDLE;
   if (n_idx < 0) return ZCG_EINVAL;
+  if (opts && (opts->workspace_bytes < 0 || (opts->workspace_bytes > 0 && !opts->workspace_dev)))
+    return ZCG_EINVAL;
   if (n_idx == 0) return ZCG_OK;
   if (!idx_dev || !out_dev) return ZCG_EINVAL;
   if ((uintptr_t)idx_dev % 8 || (uintptr_t)order_dev % 8) return ZCG_EALIGN;
@@ -210,15 +249,29 @@ static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64
   const uintptr_t o0 = (uintptr_t)out_dev, o1 = o0 + (uintptr_t)(n_idx * t->row_bytes);
   const uintptr_t t0 = (uintptr_t)t->dev, t1 = t0 + (uintptr_t)(t->n_rows * t->row_bytes);
   if (o0 < t1 && t0 < o1) return ZCG_EALIAS;
-  const bool host_resident = t->kind != ZCG_KIND_DEVICE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!order_dev && wants_order(t, n_idx, opts)) {
+    // the order lives at the start of the workspace, the builder's scratch behind it
+    int64_t* order = static_cast<int64_t*>(opts->workspace_dev);
+    char* scratch = static_cast<char*>(opts->workspace_dev) + (n_idx * 8 + 255) / 256 * 256;
+    hipError_t e = zcg_order_launch(idx_dev, n_idx, t->n_rows, order, scratch, s);
+    if (e != hipSuccess) return zcg_fail_hip(e);
+    order_dev = order;
+  }
   zcg_plan plan;
-  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, host_resident, order_dev != nullptr, opts,
-                         &plan);
+  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, t->host_resident, order_dev != nullptr,
+                         opts, &plan);
   if (rc) return rc;
   if (order_dev && plan.variant == ZCG_VARIANT_NAIVE) return ZCG_EINVAL;
   hipError_t e = zcg_launch_gather(plan, t->dev, idx_dev, order_dev, n_idx, out_dev, t->row_bytes,
-                                   t->elem, static_cast<hipStream_t>(stream));
+                                   t->elem, s);
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
+}
+
+int zcg_gather_workspace_bytes(int64_t n_idx, int64_t* bytes) {
+  if (n_idx < 0 || !bytes) return ZCG_EINVAL;
+  *bytes = n_idx ? (n_idx * 8 + 255) / 256 * 256 + zcg_order_scratch_bytes(n_idx) : 0;
+  return ZCG_OK;
 }
 
 int zcg_gather_ex(const zcg_table* t, const int64_t* idx_dev, int64_t n_idx, void* out_dev,
@@ -266,47 +319,6 @@ int zcg_validate_indices(const zcg_table* t, const int64_t* idx_dev, int64_t n_i
   return ZCG_OK;
 }
 
-int zcg_measure_h2d(int64_t bytes, int reps, int device, double* gb_per_s) {
-  if (bytes <= 0 || reps < 1 || reps > 1000 || device < 0 || !gb_per_s) return ZCG_EINVAL;
-  *gb_per_s = 0.0;
-  DeviceScope scope(device);
-  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
-  void *h = nullptr, *d = nullptr;
-  hipStream_t s = nullptr;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  std::vector<float> ms;
-  hipError_t e = hipHostMalloc(&h, (size_t)bytes, hipHostMallocDefault);
-  if (e == hipSuccess) e = hipMalloc(&d, (size_t)bytes);
-  if (e == hipSuccess) e = hipStreamCreate(&s);
-  if (e == hipSuccess) e = hipEventCreate(&e0);
-  if (e == hipSuccess) e = hipEventCreate(&e1);
-  if (e == hipSuccess) {
-    // touch the pages so the first timed copy does not pay for faults
-    for (int64_t i = 0; i < bytes; i += 4096) static_cast<volatile char*>(h)[i] = (char)i;
-    e = hipMemcpyAsync(d, h, (size_t)bytes, hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
-  }
-  for (int r = 0; r < reps && e == hipSuccess; ++r) {
-    e = hipEventRecord(e0, s);
-    if (e == hipSuccess) e = hipMemcpyAsync(d, h, (size_t)bytes, hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipEventRecord(e1, s);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    float t = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
-    if (e == hipSuccess) ms.push_back(t);
-  }
-  if (e1) (void)hipEventDestroy(e1);
-  if (e0) (void)hipEventDestroy(e0);
-  if (s) (void)hipStreamDestroy(s);
-  if (d) (void)hipFree(d);
-  if (h) (void)hipHostFree(h);
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  std::sort(ms.begin(), ms.end());
-  const double med = ms[ms.size() / 2];
-  *gb_per_s = (double)bytes / (med * 1e-3) / 1e9;
-  return ZCG_OK;
-}
-
 int zcg_device_cu_count(int device, int* n_cus) {
   if (device < 0 || !n_cus) return ZCG_EINVAL;
   int v = 0;
@@ -339,100 +351,6 @@ int zcg_stream_destroy(void* stream) {
   hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
   if (e == hipSuccess) e = hipStreamDestroy(static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
-}
-
-int zcg_synthetic_compute(void* stream, int blocks, int64_t iters, float* sink_dev) {
-  if (blocks < 1 || blocks > (1 << 20) || iters < 0 || iters > ((int64_t)1 << 32) || !sink_dev)
-    return ZCG_EINVAL;
-  hipError_t e = zcg_launch_synthetic_compute(static_cast<hipStream_t>(stream), blocks, iters, sink_dev);
-  return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
-}
-
-int zcg_measure_host_read_latency(int device, int64_t hops, double* microseconds) {
-  if (device < 0 || hops < 16 || hops > (1 << 22) || !microseconds) return ZCG_EINVAL;
-  *microseconds = 0.0;
-  DeviceScope scope(device);
-  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
-  // a random cycle over 2^16 slots, one slot per 4 KiB page of a 256 MiB mapped host buffer
-  constexpr int64_t kSlots = 1 << 16, kStrideWords = 4096 / 8;
-  uint64_t *host = nullptr, *dev_view = nullptr, *result = nullptr;
-  hipStream_t s = nullptr;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  float ms = 0.f;
-  hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&host), (size_t)kSlots * 4096,
-                               hipHostMallocMapped | hipHostMallocCoherent);
-  if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void**>(&dev_view), host, 0);
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&result), sizeof(uint64_t));
-  if (e == hipSuccess) e = hipStreamCreate(&s);
-  if (e == hipSuccess) e = hipEventCreate(&e0);
-  if (e == hipSuccess) e = hipEventCreate(&e1);
-  if (e == hipSuccess) {
-    std::vector<uint64_t> perm((size_t)kSlots);
-    for (int64_t i = 0; i < kSlots; ++i) perm[(size_t)i] = (uint64_t)i;
-    uint64_t x = 0x9E3779B97F4A7C15ull;
-    for (int64_t i = kSlots - 1; i > 0; --i) {  // Fisher-Yates with a xorshift stream
-      x ^= x << 13; x ^= x >> 7; x ^= x << 17;
-      std::swap(perm[(size_t)i], perm[(size_t)(x % (uint64_t)(i + 1))]);
-    }
-    for (int64_t i = 0; i < kSlots; ++i)  // perm order becomes one cycle through all slots
-      host[perm[(size_t)i] * kStrideWords] = perm[(size_t)((i + 1) % kSlots)];
-    e = zcg_launch_chase(s, dev_view, kStrideWords, 64, result);  // warm-up
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
-    if (e == hipSuccess) e = hipEventRecord(e0, s);
-    if (e == hipSuccess) e = zcg_launch_chase(s, dev_view, kStrideWords, hops, result);
-    if (e == hipSuccess) e = hipEventRecord(e1, s);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-  }
-  if (e1) (void)hipEventDestroy(e1);
-  if (e0) (void)hipEventDestroy(e0);
-  if (s) (void)hipStreamDestroy(s);
-  if (result) (void)hipFree(result);
-  if (host) (void)hipHostFree(host);
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  *microseconds = (double)ms * 1e3 / (double)hops;
-  return ZCG_OK;
-}
-
-int zcg_measure_host_stream_read(int device, int64_t bytes, int reps, double* gb_per_s) {
-  if (device < 0 || bytes < 4096 || bytes % 4096 || reps < 1 || reps > 1000 || !gb_per_s)
-    return ZCG_EINVAL;
-  *gb_per_s = 0.0;
-  DeviceScope scope(device);
-  if (scope.err != hipSuccess) return zcg_fail_hip(scope.err);
-  void *host = nullptr, *dev_view = nullptr, *dst = nullptr;
-  hipStream_t s = nullptr;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  std::vector<float> ms;
-  hipError_t e = hipHostMalloc(&host, (size_t)bytes, hipHostMallocMapped | hipHostMallocCoherent);
-  if (e == hipSuccess) e = hipHostGetDevicePointer(&dev_view, host, 0);
-  if (e == hipSuccess) e = hipMalloc(&dst, (size_t)bytes);
-  if (e == hipSuccess) e = hipStreamCreate(&s);
-  if (e == hipSuccess) e = hipEventCreate(&e0);
-  if (e == hipSuccess) e = hipEventCreate(&e1);
-  if (e == hipSuccess) {
-    for (int64_t i = 0; i < bytes; i += 4096) static_cast<volatile char*>(host)[i] = (char)i;
-    e = zcg_launch_stream_read(s, dev_view, dst, bytes, 2048);  // warm-up
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
-  }
-  for (int r = 0; r < reps && e == hipSuccess; ++r) {
-    e = hipEventRecord(e0, s);
-    if (e == hipSuccess) e = zcg_launch_stream_read(s, dev_view, dst, bytes, 2048);
-    if (e == hipSuccess) e = hipEventRecord(e1, s);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    float t = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
-    if (e == hipSuccess) ms.push_back(t);
-  }
-  if (e1) (void)hipEventDestroy(e1);
-  if (e0) (void)hipEventDestroy(e0);
-  if (s) (void)hipStreamDestroy(s);
-  if (dst) (void)hipFree(dst);
-  if (host) (void)hipHostFree(host);
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  std::sort(ms.begin(), ms.end());
-  *gb_per_s = (double)bytes / ((double)ms[ms.size() / 2] * 1e-3) / 1e9;
-  return ZCG_OK;
 }
 
 int zcg_pinned_alloc(int64_t bytes, void** host_ptr) {

@@ -115,7 +115,7 @@ void gather_rows_cpu(const char* table, int64_t row_bytes, const int64_t* idx, i
 int check_call(const zcg_table* t, const int64_t* idx_host, int64_t n_idx, void* staging,
                void* out_dev) {
   if (!zcg_is_live(t)) return ZCG_EHANDLE;
-  if (t->kind == ZCG_KIND_DEVICE || !t->host) return ZCG_EINVAL;
+  if (!t->host_resident || !t->host) return ZCG_EINVAL;
   if (n_idx < 0) return ZCG_EINVAL;
   if (n_idx > 0 && (!idx_host || !staging || !out_dev)) return ZCG_EINVAL;
   for (int64_t i = 0; i < n_idx; ++i)

@@ -540,46 +540,6 @@ zcg_k_validate(const int64_t* __restrict__ idx, int64_t n_idx, int64_t n_rows,
   if (bad) atomicAdd(n_bad, bad);
 }
 
-// ALU-bound stand-in for a training kernel: a chain of dependent FMAs per lane.
-__global__ void __launch_bounds__(kBlock)
-zcg_k_synthetic_compute(int64_t iters, float* __restrict__ sink) {
-  float a = 1.0f + (float)threadIdx.x * 1e-6f, b = 0.999999f, c = 1e-7f;
-  for (int64_t i = 0; i < iters; ++i) a = __builtin_fmaf(a, b, c);
-  atomicAdd(&sink[threadIdx.x], a);
-}
-
-// One lane follows a chain of dependent loads: next = chain[next * stride].
-__global__ void zcg_k_chase(const uint64_t* __restrict__ chain, int64_t stride_words, int64_t hops,
-                            uint64_t* __restrict__ result) {
-  uint64_t p = 0;
-  for (int64_t i = 0; i < hops; ++i)
-    p = *(const volatile uint64_t __attribute__((address_space(1)))*)(chain + p * stride_words);
-  *result = p;
-}
-
-// Streams n_chunks consecutive 8-byte chunks from src to dst: the gather's own access shape
-// (8-byte lanes, two wave passes in flight, non-temporal stores) with nothing to look up.
-__global__ void __launch_bounds__(kBlock)
-zcg_k_stream_read(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int64_t n_chunks) {
-  constexpr int W = 8, U = 2;
-  typedef typename vec_of<W>::type vec;
-  const int64_t lanes = (int64_t)gridDim.x * kBlock;
-  const uint8_t* dummy = reinterpret_cast<const uint8_t*>(zcg_dummy_chunk);
-  for (int64_t c0 = (int64_t)blockIdx.x * kBlock + threadIdx.x; c0 < n_chunks; c0 += lanes * U) {
-    vec v[U];
-    bool ok[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int64_t c = c0 + (int64_t)u * lanes;
-      ok[u] = c < n_chunks;
-      v[u] = load_chunk<W, 0>(ok[u] ? src + c * W : dummy);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (ok[u]) store_chunk<W, true>(dst + (c0 + (int64_t)u * lanes) * W, v[u]);
-  }
-}
-
 // Bytes of a row's line-aligned span that one wavefront takes when p.row_splits wavefronts
 // share the row: whole passes of 64 * W * U bytes, so every piece runs the same loop, and
 // enough of them to cover the longest span (row_bytes plus less than a line).
@@ -769,24 +729,6 @@ hipError_t zcg_launch_gather(const zcg_plan& p, const void* table, const int64_t
     case 1: return launch_rows_u<1>(p, t, idx, order, n_idx, o, row_bytes, stream);
     default: return hipErrorInvalidValue;
   }
-}
-
-hipError_t zcg_launch_chase(hipStream_t stream, const uint64_t* chain, int64_t stride_words,
-                            int64_t hops, uint64_t* result) {
-  zcg_k_chase<<<dim3(1), dim3(1), 0, stream>>>(chain, stride_words, hops, result);
-  return hipGetLastError();
-}
-
-hipError_t zcg_launch_stream_read(hipStream_t stream, const void* src, void* dst, int64_t bytes,
-                                  int blocks) {
-  zcg_k_stream_read<<<dim3((unsigned)blocks), dim3(kBlock), 0, stream>>>(
-      static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst), bytes / 8);
-  return hipGetLastError();
-}
-
-hipError_t zcg_launch_synthetic_compute(hipStream_t stream, int blocks, int64_t iters, float* sink) {
-  zcg_k_synthetic_compute<<<dim3((unsigned)blocks), dim3(kBlock), 0, stream>>>(iters, sink);
-  return hipGetLastError();
 }
 
 hipError_t zcg_launch_validate(const int64_t* idx, int64_t n_idx, int64_t n_rows,

@@ -1,78 +1,318 @@
 // Processing order for the ordered gather: a permutation `order` of [0, n) such
-// that idx[order[k]] ascends with k. Rows are then fetched in ascending table
-// order -- neighbouring work items touch neighbouring lines and pages of the host
-// table -- while every row still lands at its own position of the output.
-// The sort itself is a library primitive (rocPRIM radix sort of (index, position)
-// pairs); all memory it needs comes from the caller's workspace.
+// that idx[order[k]] ascends with k, equal entries in list order. Rows are then
+// fetched in ascending table order -- neighbouring work items touch neighbouring
+// lines and pages of the host table, so rows that share a line or a 256-byte pair
+// of lines share a link request -- while every row still lands at its own
+// position of the output.
+//
+// The order is built by a least-significant-digit radix sort written for
+// wave64: digits of up to 8 bits, and per digit three kernels,
+//   count   : every block histograms the digit over its tile of the list,
+//   offsets : per bin, an exclusive prefix of the counts over the blocks,
+//   scatter : every block recounts its tile per wavefront, turns the counts into
+//             output positions (bin base + blocks before + wavefronts before) and
+//             moves its elements; inside a wavefront elements are ranked 64 at a
+//             time with ballots, so the pass is stable and its result does not
+//             depend on scheduling.
+// No kernel waits for another block, nothing is cleared with a memory-set, and all
+// temporary memory is the caller's (or the static array of the allocation-free
+// entry point): the whole build is a chain of plain kernel launches on one stream.
+// Between passes an element travels as (32-bit key, 32-bit list position); the
+// output array doubles as the second buffer of the ping-pong. Tables of 2^32 rows
+// or more carry the position only and look the key up again in the list.
 #include <hip/hip_runtime.h>
-
-#include <cstring>  // rocPRIM's headers use memset without including it
-
-#include <rocprim/rocprim.hpp>
 
 #include "zcg_internal.h"
 
 namespace {
 
-__global__ void __launch_bounds__(256) zcg_k_iota(int64_t* __restrict__ p, int64_t n) {
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) p[i] = i;
+constexpr int kBlock = 256;      // 4 wavefronts
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kMaxBins = 256;    // digits of at most 8 bits
+constexpr int64_t kAlign = 256;
+constexpr int64_t kMaxBlocks = 1024;  // cap on the grid: the per-bin prefix is one block-wide scan
+
+int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Elements each wavefront owns: 1024, more for lists beyond 4 M entries so that the grid
+// stays within kMaxBlocks; always a multiple of the wave size.
+int64_t wave_span(int64_t n) {
+  const int64_t need = (n + kMaxBlocks * kWavesPerBlock - 1) / (kMaxBlocks * kWavesPerBlock);
+  return need <= 1024 ? 1024 : round_up(need, kWave);
+}
+int64_t grid_blocks(int64_t n) {
+  const int64_t per_block = wave_span(n) * kWavesPerBlock;
+  return (n + per_block - 1) / per_block;
 }
 
-constexpr int64_t kAlign = 256;
-int64_t round_up(int64_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+// Where a pass reads its elements from.
+enum Src { SRC_LIST = 0,     // the index list itself: key = idx[i], position = i
+           SRC_CARRIED = 1,  // (key32[i], pos[i]) written by the previous pass
+           SRC_REFETCH = 2   // pos[i] written by the previous pass, key = idx[pos[i]]
+};
+// What a pass writes.
+enum Dst { DST_CARRIED = 0,  // key32 and position
+           DST_POS = 1,      // position only (keys of more than 32 bits)
+           DST_ORDER = 2     // the final int64 order
+};
 
-hipError_t sort_temp_bytes(int64_t n, size_t* bytes) {
-  *bytes = 0;
-  return rocprim::radix_sort_pairs(nullptr, *bytes, static_cast<const uint64_t*>(nullptr),
-                                   static_cast<uint64_t*>(nullptr),
-                                   static_cast<const int64_t*>(nullptr),
-                                   static_cast<int64_t*>(nullptr), (size_t)n, 0, 64, nullptr);
+struct PassIO {
+  const int64_t* idx;
+  const uint32_t* src_keys;
+  const uint32_t* src_pos;
+  uint32_t* dst_keys;
+  uint32_t* dst_pos;
+  int64_t* order;
+};
+
+template <int SRC>
+__device__ __forceinline__ void fetch(const PassIO& io, int64_t i, uint64_t& key, uint32_t& pos) {
+  if constexpr (SRC == SRC_LIST) {
+    key = (uint64_t)io.idx[i];
+    pos = (uint32_t)i;
+  } else if constexpr (SRC == SRC_CARRIED) {
+    key = io.src_keys[i];
+    pos = io.src_pos[i];
+  } else {
+    pos = io.src_pos[i];
+    key = (uint64_t)io.idx[pos];
+  }
+}
+
+// Lanes of the wavefront that are active and hold the same digit as this lane (8 ballots).
+__device__ __forceinline__ uint64_t same_digit_lanes(unsigned d, bool active) {
+  uint64_t m = __ballot(active);
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    const bool bit = (d >> b) & 1u;
+    const uint64_t with_bit = __ballot(active && bit);
+    m &= bit ? with_bit : ~with_bit;
+  }
+  return m;
+}
+
+// Exclusive prefix sum over the 256 threads of a block; *total (may be null) gets the sum.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_sums,
+                                                         uint32_t* total) {
+  const unsigned lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  uint32_t incl = v;
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d, kWave);
+    if (lane >= (unsigned)d) incl += up;
+  }
+  if (lane == kWave - 1) wave_sums[w] = incl;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int k = 0; k < kWavesPerBlock; ++k) {
+    const uint32_t s = wave_sums[k];
+    before += (unsigned)k < w ? s : 0u;
+    all += s;
+  }
+  if (total) *total = all;
+  __syncthreads();  // wave_sums may be reused by the caller
+  return before + incl - v;
+}
+
+// counts[bin * n_blocks + block] = entries of the block's tile whose digit is `bin`.
+template <int SRC>
+__global__ void __launch_bounds__(kBlock)
+zcg_k_order_count(PassIO io, int64_t n, int64_t span, int shift, unsigned mask,
+                  uint32_t* __restrict__ counts) {
+  __shared__ uint32_t hist[kMaxBins];
+  hist[threadIdx.x] = 0;
+  __syncthreads();
+  const unsigned lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t begin = ((int64_t)blockIdx.x * kWavesPerBlock + w) * span;
+  const int64_t end = begin + span < n ? begin + span : n;
+  for (int64_t i = begin + lane; i < end; i += kWave) {
+    uint64_t key;
+    uint32_t pos;
+    fetch<SRC>(io, i, key, pos);
+    atomicAdd(&hist[(unsigned)(key >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  if (threadIdx.x <= mask) counts[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = hist[threadIdx.x];
+}
+
+// One block per bin: counts[bin][0..n_blocks) becomes its exclusive prefix over the blocks,
+// totals[bin] the bin's size. n_blocks <= kMaxBlocks = 4 entries per thread.
+__global__ void __launch_bounds__(kBlock)
+zcg_k_order_offsets(uint32_t* __restrict__ counts, uint32_t* __restrict__ totals, int n_blocks) {
+  __shared__ uint32_t wave_sums[kWavesPerBlock];
+  constexpr int kPer = (int)(kMaxBlocks / kBlock);
+  uint32_t* row = counts + (int64_t)blockIdx.x * n_blocks;
+  uint32_t v[kPer], sum = 0;
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const int j = (int)threadIdx.x * kPer + k;
+    v[k] = j < n_blocks ? row[j] : 0u;
+    sum += v[k];
+  }
+  uint32_t total;
+  uint32_t run = block_exclusive_scan(sum, wave_sums, &total);
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const int j = (int)threadIdx.x * kPer + k;
+    if (j < n_blocks) row[j] = run;
+    run += v[k];
+  }
+  if (threadIdx.x == 0) totals[blockIdx.x] = total;
+}
+
+template <int SRC, int DST>
+__global__ void __launch_bounds__(kBlock)
+zcg_k_order_scatter(PassIO io, int64_t n, int64_t span, int shift, unsigned mask,
+                    const uint32_t* __restrict__ offsets, const uint32_t* __restrict__ totals) {
+  __shared__ uint32_t next[kWavesPerBlock][kMaxBins];  // per wavefront and bin: next output position
+  __shared__ uint32_t wave_sums[kWavesPerBlock];
+  const unsigned lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const unsigned bin = threadIdx.x;
+  const unsigned n_bins = mask + 1u;
+#pragma unroll
+  for (int k = 0; k < kWavesPerBlock; ++k) next[k][bin] = 0;
+  // where each bin starts in the output: exclusive prefix of the bin sizes
+  const uint32_t bin_base = block_exclusive_scan(bin < n_bins ? totals[bin] : 0u, wave_sums, nullptr);
+
+  const int64_t begin = ((int64_t)blockIdx.x * kWavesPerBlock + w) * span;
+  const int64_t end = begin + span < n ? begin + span : n;
+  // 1. every wavefront counts the digits of its own stretch of the tile
+  for (int64_t i = begin + lane; i < end; i += kWave) {
+    uint64_t key;
+    uint32_t pos;
+    fetch<SRC>(io, i, key, pos);
+    atomicAdd(&next[w][(unsigned)(key >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  // 2. counts -> first output position of (wavefront, bin): the bin's base, the entries of
+  //    earlier blocks, the entries of earlier wavefronts of this block
+  if (bin < n_bins) {
+    uint32_t run = bin_base + offsets[(int64_t)bin * gridDim.x + blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < kWavesPerBlock; ++k) {
+      const uint32_t c = next[k][bin];
+      next[k][bin] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+  // 3. every wavefront walks its stretch again in list order, 64 entries at a time; entries of
+  //    one step with the same digit are ranked by lane, and only this wavefront touches next[w]
+  for (int64_t i0 = begin; i0 < end; i0 += kWave) {
+    const int64_t i = i0 + lane;
+    const bool active = i < end;
+    uint64_t key = 0;
+    uint32_t pos = 0;
+    if (active) fetch<SRC>(io, i, key, pos);
+    const unsigned d = (unsigned)(key >> shift) & mask;
+    const uint64_t peers = same_digit_lanes(d, active);
+    const unsigned rank = (unsigned)__popcll(peers & (((uint64_t)1 << lane) - 1u));
+    const int leader = __ffsll((unsigned long long)peers) - 1;
+    uint32_t first = 0;
+    if (active && (int)lane == leader) first = atomicAdd(&next[w][d], (uint32_t)__popcll(peers));
+    first = __shfl(first, leader < 0 ? 0 : leader, kWave);
+    if (active) {
+      const uint32_t at = first + rank;
+      if constexpr (DST == DST_ORDER) {
+        io.order[at] = (int64_t)pos;
+      } else {
+        if constexpr (DST == DST_CARRIED) io.dst_keys[at] = (uint32_t)key;
+        io.dst_pos[at] = pos;
+      }
+    }
+  }
+}
+
+template <int SRC>
+hipError_t launch_pass(int dst, const PassIO& io, int64_t n, int64_t span, int shift, unsigned mask,
+                       uint32_t* counts, uint32_t* totals, hipStream_t s) {
+  const dim3 grid((unsigned)grid_blocks(n)), block(kBlock);
+  zcg_k_order_count<SRC><<<grid, block, 0, s>>>(io, n, span, shift, mask, counts);
+  zcg_k_order_offsets<<<dim3(mask + 1u), block, 0, s>>>(counts, totals, (int)grid.x);
+  switch (dst) {
+    case DST_CARRIED:
+      zcg_k_order_scatter<SRC, DST_CARRIED><<<grid, block, 0, s>>>(io, n, span, shift, mask, counts, totals);
+      break;
+    case DST_POS:
+      zcg_k_order_scatter<SRC, DST_POS><<<grid, block, 0, s>>>(io, n, span, shift, mask, counts, totals);
+      break;
+    default:
+      zcg_k_order_scatter<SRC, DST_ORDER><<<grid, block, 0, s>>>(io, n, span, shift, mask, counts, totals);
+      break;
+  }
+  return hipGetLastError();
 }
 
 }  // namespace
+
+int64_t zcg_order_scratch_bytes(int64_t n_idx) {
+  if (n_idx <= 0) return 0;
+  // one (key32, position) buffer, the per-bin per-block counts, the bin sizes
+  return round_up(n_idx * 8, kAlign) + round_up(kMaxBins * grid_blocks(n_idx) * 4, kAlign) +
+         round_up(kMaxBins * 4, kAlign);
+}
+
+hipError_t zcg_order_launch(const int64_t* idx, int64_t n, int64_t n_rows, int64_t* order,
+                            void* scratch, hipStream_t s) {
+  // bits that can differ between valid indices, split evenly over digits of at most 8 bits
+  int bits = 1;
+  while (bits < 63 && ((int64_t)1 << bits) < n_rows) ++bits;
+  const int passes = (bits + 7) / 8;
+  const bool wide_keys = bits > 32;
+  char* ws = static_cast<char*>(scratch);
+  uint32_t* buf_a = reinterpret_cast<uint32_t*>(ws);
+  uint32_t* counts = reinterpret_cast<uint32_t*>(ws + round_up(n * 8, kAlign));
+  uint32_t* totals = counts + round_up(kMaxBins * grid_blocks(n) * 4, kAlign) / 4;
+  uint32_t* buf_o = reinterpret_cast<uint32_t*>(order);  // the output array is the second buffer
+  const int64_t span = wave_span(n);
+
+  int shift = 0;
+  const uint32_t* src = nullptr;
+  for (int p = 0; p < passes; ++p) {
+    const int digit_bits = (bits - shift + (passes - p) - 1) / (passes - p);
+    const unsigned mask = (1u << digit_bits) - 1u;
+    const bool last = p == passes - 1;
+    // passes alternate between the two buffers such that the last one reads buffer A
+    uint32_t* dst = ((passes - 2 - p) % 2 == 0) ? buf_a : buf_o;
+    PassIO io;
+    io.idx = idx;
+    io.src_keys = src;
+    io.src_pos = src ? src + (wide_keys ? 0 : n) : nullptr;
+    io.dst_keys = last ? nullptr : dst;
+    io.dst_pos = last ? nullptr : dst + (wide_keys ? 0 : n);
+    io.order = order;
+    const int dst_kind = last ? DST_ORDER : (wide_keys ? DST_POS : DST_CARRIED);
+    hipError_t e;
+    if (p == 0) e = launch_pass<SRC_LIST>(dst_kind, io, n, span, shift, mask, counts, totals, s);
+    else if (wide_keys) e = launch_pass<SRC_REFETCH>(dst_kind, io, n, span, shift, mask, counts, totals, s);
+    else e = launch_pass<SRC_CARRIED>(dst_kind, io, n, span, shift, mask, counts, totals, s);
+    if (e != hipSuccess) return e;
+    src = dst;
+    shift += digit_bits;
+  }
+  return hipSuccess;
+}
 
 extern "C" {
 
 int zcg_order_workspace_bytes(int64_t n_idx, int64_t* bytes) {
   if (n_idx < 0 || !bytes) return ZCG_EINVAL;
-  *bytes = 0;
-  if (n_idx == 0) return ZCG_OK;
-  size_t temp = 0;
-  hipError_t e = sort_temp_bytes(n_idx, &temp);
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  *bytes = 2 * round_up(n_idx * 8) + round_up((int64_t)temp);
+  *bytes = zcg_order_scratch_bytes(n_idx);
   return ZCG_OK;
 }
 
 int zcg_make_order(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_t* order_dev,
                    void* workspace_dev, int64_t workspace_bytes, void* stream) {
-  if (n_idx < 0 || n_rows < 1) return ZCG_EINVAL;
+  if (n_idx < 0 || n_rows < 1 || n_idx > (int64_t)UINT32_MAX) return ZCG_EINVAL;
   if (n_idx == 0) return ZCG_OK;
   if (!idx_dev || !order_dev || !workspace_dev) return ZCG_EINVAL;
   if (((uintptr_t)idx_dev | (uintptr_t)order_dev) % 8 || (uintptr_t)workspace_dev % kAlign)
     return ZCG_EALIGN;
-  size_t temp = 0;
-  hipError_t e = sort_temp_bytes(n_idx, &temp);
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  const int64_t seg = round_up(n_idx * 8);
-  if (workspace_bytes < 2 * seg + round_up((int64_t)temp)) return ZCG_EINVAL;
-  char* ws = static_cast<char*>(workspace_dev);
-  uint64_t* keys_out = reinterpret_cast<uint64_t*>(ws);
-  int64_t* iota = reinterpret_cast<int64_t*>(ws + seg);
-  void* sort_temp = ws + 2 * seg;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  int64_t blocks = (n_idx + 255) / 256;
-  if (blocks > 4096) blocks = 4096;
-  zcg_k_iota<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(iota, n_idx);
-  e = hipGetLastError();
-  if (e != hipSuccess) return zcg_fail_hip(e);
-  // valid indices are below n_rows: sort only the bits that can differ
-  int end_bit = 1;
-  while (end_bit < 63 && ((int64_t)1 << end_bit) < n_rows) ++end_bit;
-  e = rocprim::radix_sort_pairs(sort_temp, temp, reinterpret_cast<const uint64_t*>(idx_dev),
-                                keys_out, static_cast<const int64_t*>(iota), order_dev,
-                                (size_t)n_idx, 0, end_bit, s);
+  if (workspace_bytes < zcg_order_scratch_bytes(n_idx)) return ZCG_EINVAL;
+  hipError_t e = zcg_order_launch(idx_dev, n_idx, n_rows, order_dev, workspace_dev,
+                                  static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
 }
 

@@ -26,8 +26,8 @@ struct zcg_pipeline {
   bool own_stream = false;
   // Rows of at most one line over the host link are bound by the request rate; walked in
   // ascending table order, neighbouring rows share lines and pairs of lines (measured +12 %
-  // on 128-byte rows, +30 % on 32-byte rows, sort included). The pipeline owns the memory
-  // the sort needs, so it does this by itself.
+  // on 128-byte rows, +30 % on 32-byte rows, order build included). The pipeline owns the
+  // memory the order builder needs, so it does this by itself.
   bool sorts = false;
   int64_t sort_ws_bytes = 0;
   hipStream_t gather_stream = nullptr;
@@ -183,7 +183,7 @@ int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, voi
   p->max_rows = max_rows;
   p->n_buffers = n_buffers;
   p->slots.resize((size_t)n_buffers);
-  p->sorts = t->kind != ZCG_KIND_DEVICE && t->row_bytes <= 128;
+  p->sorts = t->host_resident && t->row_bytes <= 128 && max_rows <= (int64_t)UINT32_MAX;
   if (p->sorts && zcg_order_workspace_bytes(max_rows, &p->sort_ws_bytes) != ZCG_OK) p->sorts = false;
   hipError_t e = hipSuccess;
   if (gather_stream) {

@@ -28,7 +28,7 @@ def closed_form(seed, pos, dtype):
     return (((zz >> U64(53)).astype(np.int64) - 1024).astype(np.float64) * 2.0 ** -10).astype(np.float16)
 
 
-def check_config(cfg, lists, n_rows=None, also_hbm=False):
+def check_config(cfg, lists, n_rows=None, also_hbm=False, full_oracle_on=None):
     n_rows = n_rows or cfg.n_rows
     if not torch.cuda.is_available():
         pytest.fail("GPU tests need a GPU")
@@ -53,17 +53,21 @@ def check_config(cfg, lists, n_rows=None, also_hbm=False):
             assert idx.min() >= 0 and idx.max() < n_rows
             idx_dev = torch.from_numpy(idx).cuda()
             assert z.validate_indices(table, idx_dev) == 0
-            want = np.empty((idx.size, cfg.dim), dtype=ndt)
-            gather_bytes(table.host_ptr, n_rows, cfg.row_bytes, idx, want.ctypes.data, n_threads=8)
+            full = full_oracle_on is None or b in full_oracle_on
+            if full:
+                want = np.empty((idx.size, cfg.dim), dtype=ndt)
+                gather_bytes(table.host_ptr, n_rows, cfg.row_bytes, idx, want.ctypes.data, n_threads=8)
             for t in ([table, hbm] if hbm else [table]):
                 out = torch.zeros((idx.size, cfg.dim), dtype=tdt, device="cuda")
                 z.gather(t, idx_dev, out)
                 torch.cuda.synchronize()
                 got = out.cpu().numpy()
-                assert got.tobytes() == want.tobytes(), f"{cfg.name} list {b}: GPU differs from oracle"
+                if full:
+                    assert got.tobytes() == want.tobytes(), f"{cfg.name} list {b}: GPU differs from oracle"
             # sampled elements against the closed form
-            rows = rng.integers(0, idx.size, 4096)
-            cols = rng.integers(0, cfg.dim, 4096)
+            n_samples = 4096 if full else 16384
+            rows = rng.integers(0, idx.size, n_samples)
+            cols = rng.integers(0, cfg.dim, n_samples)
             pos = idx[rows] * cfg.dim + cols
             assert (got[rows, cols] == closed_form(cfg.seed, pos, cfg.dtype)).all()
         if hbm:
@@ -82,14 +86,15 @@ def test_configs_1_to_3_full_size(k):
 
 
 def test_config_4_beyond_hbm_scale():
-    """111 M x 128 fp32 = 56.8 GB of pinned host memory; 3 of the 50 minibatches are
-    checked in full (the benchmark runs all 50)."""
+    """111 M x 128 fp32 = 56.8 GB of pinned host memory, the 50 minibatches the benchmark runs:
+    three are compared byte for byte with the oracle, all 50 on 16,384 sampled elements each
+    against the closed form of the table."""
     cfg = wl.config(4)
     g = wl.PowerLawGraph(cfg.n_rows, cfg.graph[0], cfg.graph[1], cfg.seed)
-    lists = [g.sample_minibatch(cfg.n_seeds, cfg.fanout, b)[0] for b in (0, 1, 49)]
+    lists = [g.sample_minibatch(cfg.n_seeds, cfg.fanout, b)[0] for b in range(50)]
     g.close()
     assert max(int(a.max()) for a in lists) * cfg.row_bytes > 2 ** 35  # offsets far beyond 32 bits
-    check_config(cfg, lists)
+    check_config(cfg, lists, full_oracle_on=(0, 1, 49))
 
 
 @pytest.mark.parametrize("cfg", wl.sweep_configs(), ids=lambda c: c.name)

@@ -10,6 +10,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 z = pytest.importorskip("paper_2103_03330_amd")
+from paper_2103_03330_amd import probe  # noqa: E402
 
 ALL_VARIANTS = [z.VARIANT_AUTO, z.VARIANT_NAIVE, z.VARIANT_ROWVEC, z.VARIANT_ALIGNED,
                 z.VARIANT_HALFLINE]
@@ -59,6 +60,9 @@ SHAPES = [
     # 1-byte (int8 / fp8) and 8-byte elements: odd byte rows, sub-line, long, line multiples
     (3000, 1, "i8"), (3000, 37, "i8"), (2500, 100, "i8"), (2000, 401, "i8"), (900, 2049, "i8"),
     (2000, 512, "i8"), (1500, 1, "f64"), (1500, 50, "f64"), (800, 301, "f64"),
+    # the row sizes of the alignment experiment (Section 4.2): 1024 ... 1044 bytes
+    (1500, 256, "f32"), (1500, 257, "f32"), (1500, 258, "f32"), (1500, 259, "f32"), (1500, 260, "f32"),
+    (1500, 261, "f32"),
 ]
 
 
@@ -196,6 +200,81 @@ def test_unaligned_bases(byte_off):
         table.close()
 
 
+@pytest.mark.parametrize("dim", [100, 257, 602, 128, 16])
+def test_auto_on_host_resident_views_off_the_line_grid(dim):
+    """A table that starts anywhere inside a pinned allocation (zcg_table_view keeps it
+    host-resident): the default call must plan from the real address -- half-line kernel with
+    shifted stores for rows longer than a line -- and still be exact."""
+    n_rows, n_idx = 2000, 3000
+    parent = host_table(n_rows + 2, dim, "f32", seed=dim + 1)
+    try:
+        flat = parent.host_array().reshape(-1)
+        idx = wl.uniform_indices(n_idx, n_rows, seed=2)
+        idx[:2] = (0, n_rows - 1)
+        for byte_off in (4, 8, 16, 48, 64, 100, 128, 4 * dim):
+            view = z.table_view(parent, byte_off, n_rows, dim, "f32")
+            assert view.device_ptr == parent.device_ptr + byte_off
+            assert view.host_ptr == parent.host_ptr + byte_off
+            sub = np.ascontiguousarray(flat[byte_off // 4: byte_off // 4 + n_rows * dim].reshape(n_rows, dim))
+            want = oracle_gather(sub, idx)
+            buf = torch.zeros(n_idx * dim + 64, dtype=torch.float32, device="cuda")
+            for out_off in (0, byte_off % 64):
+                out = buf[out_off // 4: out_off // 4 + n_idx * dim].view(n_idx, dim)
+                plan = z.plan_gather(view, n_idx, out)
+                if dim * 4 > 128 and (dim * 4) % 128:
+                    assert plan["variant"] == z.VARIANT_HALFLINE, (byte_off, plan)
+                    if byte_off % 8 or out_off % 8:
+                        assert plan["store_bytes"] < plan["vec_bytes"], (byte_off, plan)  # shifted stores
+                if dim == 128:  # whole-line rows: realigned only when the base is off the line grid
+                    want_variant = z.VARIANT_ROWVEC if byte_off % 128 == 0 else z.VARIANT_HALFLINE
+                    assert plan["variant"] == want_variant, (byte_off, plan)
+                buf.zero_()
+                got = run_gather(view, idx, "f32", None, out=out)
+                assert_same_bits(got, want, f"view+{byte_off} out+{out_off} dim={dim} plan={plan}")
+                assert not bool(buf[: out_off // 4].view(torch.int32).any())
+                assert not bool(buf[out_off // 4 + n_idx * dim:].view(torch.int32).any())
+            # the DMA baseline reads through the view's host address
+            staging = z.pinned_alloc(n_idx * dim * 4)
+            out = torch.zeros((n_idx, dim), dtype=torch.float32, device="cuda")
+            z.cpu_gather_memcpy(view, idx, staging, out, n_threads=2)
+            torch.cuda.synchronize()
+            assert_same_bits(out, want, f"cpu baseline on view+{byte_off}")
+            z.pinned_free(staging)
+            view.close()
+        with pytest.raises(z.ZcgError) as e:  # past the parent's end
+            z.table_view(parent, 8, n_rows + 2, dim, "f32")
+        assert e.value.status == -1
+        with pytest.raises(z.ZcgError) as e:
+            z.table_view(parent, 2, n_rows, dim, "f32")
+        assert e.value.status == -6
+        view = z.table_view(parent, 16, n_rows, dim, "f32")
+    finally:
+        parent.close()
+    # the parent is gone: the view is dead for every call, and can still be released
+    idx_dev = torch.zeros(4, dtype=torch.int64, device="cuda")
+    out = torch.zeros((4, dim), dtype=torch.float32, device="cuda")
+    with pytest.raises(z.ZcgError) as e:
+        z.gather(view, idx_dev, out)
+    assert e.value.status == -3
+    view.close()
+
+
+_KEPT_ALIVE = []  # see test_uncached_host_table
+
+
+def test_uncached_host_table():
+    """ZCG_ALLOC_UNCACHED (extended fine-grained host memory). The table is kept until the
+    process ends on purpose: memory of this kind is not handed back while the GPU may still
+    hold lines of it."""
+    n_rows, dim = 3000, 100
+    table = host_table(n_rows, dim, "f32", seed=77, flags=z.ALLOC_UNCACHED)
+    _KEPT_ALIVE.append(table)
+    idx = wl.uniform_indices(5000, n_rows, seed=4)
+    want = oracle_gather(table.host_array(), idx)
+    for variant in ALL_VARIANTS:
+        assert_same_bits(run_gather(table, idx, "f32", z.LaunchOpts(variant=variant)), want, "uncached")
+
+
 def test_hbm_resident_table_and_noncoherent_host_table():
     n_rows, dim = 6000, 602
     np_table = wl.make_table(n_rows, dim, "f32", seed=21)
@@ -280,7 +359,7 @@ def test_gather_on_a_cu_masked_stream():
             torch.cuda.synchronize()
             z.gather(table, idx_dev, out, stream=ms)
             sink = torch.zeros(256, dtype=torch.float32, device="cuda")
-            z.synthetic_compute(ms, 64, 1000, sink)
+            probe.synthetic_compute(ms, 64, 1000, sink)
             ms.close()  # waits for the stream
             assert_same_bits(out, want, f"masked stream, {len(cus)} CUs")
             assert float(sink.sum()) > 0
@@ -332,6 +411,113 @@ def test_ordered_gather_matches_oracle(n_rows, dim, dtype):
             z.make_order(idx_dev, n_rows, order, ws, ws_bytes - 256)
         assert e.value.status == -1
         z.gather_ordered(table, idx_dev, order, out, n_idx=0)  # empty: nothing to do
+    finally:
+        table.close()
+
+
+@pytest.mark.parametrize("n_rows", [1, 2, 31, 256, 257, 65_536, 100_000, 2_450_000, 20_000_000,
+                                    (1 << 32) + 5, 1 << 45])
+def test_make_order_key_widths_lengths_and_skew(n_rows):
+    """The order builder against numpy's stable argsort: 1 to 46 key bits (one to six digit
+    passes; beyond 32 bits the keys are looked up again in the list), list lengths from one entry
+    to several tiles per block and beyond 4 M entries (longer stretches per wavefront), uniform,
+    constant, two-valued and ascending / descending lists."""
+    rng = np.random.default_rng(n_rows % 1000003)
+    lengths = [1, 2, 63, 64, 65, 1023, 4096, 4097, 50_021, 300_000]
+    if n_rows in (257, 20_000_000):
+        lengths.append(4_500_000)
+    for n in lengths:
+        lists = {"uniform": rng.integers(0, n_rows, n)}
+        if n in (65, 50_021):
+            lists["constant"] = np.full(n, n_rows - 1, np.int64)
+            lists["two values"] = np.where(rng.random(n) < 0.9, 0, n_rows - 1).astype(np.int64)
+            lists["ascending"] = np.sort(lists["uniform"])
+            lists["descending"] = np.sort(lists["uniform"])[::-1].copy()
+        ws_bytes = z.order_workspace_bytes(n)
+        assert ws_bytes >= 8 * n and ws_bytes % 256 == 0
+        ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+        ws_ptr = (ws.data_ptr() + 255) // 256 * 256
+        for name, idx in lists.items():
+            idx_dev = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int64)).cuda()
+            order = torch.full((n + 2,), -5, dtype=torch.int64, device="cuda")  # guard entries
+            z.make_order(idx_dev, n_rows, order[1:], ws_ptr, ws_bytes, n_idx=n)
+            torch.cuda.synchronize()
+            o = order.cpu().numpy()
+            assert o[0] == -5 and o[-1] == -5, f"{name} n={n}: wrote outside the order array"
+            assert np.array_equal(o[1:-1], np.argsort(idx, kind="stable")), f"{name} n={n} n_rows={n_rows}"
+
+
+def test_make_order_argument_checks_and_capture():
+    n, n_rows = 20_000, 1000
+    idx = torch.from_numpy(wl.uniform_indices(n, n_rows, seed=1)).cuda()
+    order = torch.empty(n, dtype=torch.int64, device="cuda")
+    ws_bytes = z.order_workspace_bytes(n)
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    ws_ptr = (ws.data_ptr() + 255) // 256 * 256
+    for bad in (lambda: z.make_order(idx, 0, order, ws_ptr, ws_bytes),
+                lambda: z.make_order(idx, n_rows, order, ws_ptr, ws_bytes - 256),
+                lambda: z.make_order(idx, n_rows, order, ws_ptr, ws_bytes, n_idx=1 << 32),
+                lambda: z.make_order(idx, n_rows, 0, ws_ptr, ws_bytes)):
+        with pytest.raises(z.ZcgError) as e:
+            bad()
+        assert e.value.status == -1
+    with pytest.raises(z.ZcgError) as e:
+        z.make_order(idx, n_rows, order, ws_ptr + 8, ws_bytes)
+    assert e.value.status == -6
+    z.make_order(idx, n_rows, order, ws_ptr, ws_bytes, n_idx=0)  # nothing to do
+    assert z.order_workspace_bytes(0) == 0
+    # the build is kernel launches only: it can be captured, and a replay follows the list
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        z.make_order(idx, n_rows, order, ws_ptr, ws_bytes, stream=s)
+    for seed in (2, 3, 4):
+        fresh = wl.uniform_indices(n, n_rows, seed=seed)
+        idx.copy_(torch.from_numpy(fresh))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(order.cpu().numpy(), np.argsort(fresh, kind="stable")), f"replay {seed}"
+
+
+@pytest.mark.parametrize("n_rows,dim,dtype", [(3_000_000, 16, "f16"), (2_000_000, 16, "f32"),
+                                               (1_500_000, 32, "f32"), (900_000, 24, "f32")])
+def test_auto_with_lent_workspace_orders_short_rows(n_rows, dim, dtype):
+    """zcg_gather_ex, variant AUTO, workspace lent through the options: long lists of
+    host-resident rows of at most a line are walked in ascending table order. Same bytes."""
+    table = host_table(n_rows, dim, dtype, seed=dim)
+    try:
+        n = 200_003
+        idx = wl.uniform_indices(n, n_rows, seed=23)
+        want = oracle_gather(table.host_array(), idx)
+        idx_dev = torch.from_numpy(idx).cuda()
+        ws_bytes = z.gather_workspace_bytes(n)
+        ws = torch.zeros(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+        ws_ptr = (ws.data_ptr() + 255) // 256 * 256
+        for rep in range(2):
+            out = torch.full((n, dim), -7, dtype=TORCH_DT[dtype], device="cuda")
+            z.gather_ex(table, idx_dev, out, z.LaunchOpts(workspace_dev=ws_ptr, workspace_bytes=ws_bytes))
+            torch.cuda.synchronize()
+            assert_same_bits(out, want, f"auto ordered rep {rep}")
+        # the order it built is left at the start of the workspace
+        off = ws_ptr - ws.data_ptr()
+        built = ws[off: off + 8 * n].view(torch.int64).cpu().numpy()
+        assert np.array_equal(built, np.argsort(idx, kind="stable"))
+        # too little workspace, a forced kernel, a short list: the plain path, same result
+        for opts, n_use in ((z.LaunchOpts(workspace_dev=ws_ptr, workspace_bytes=ws_bytes // 2), n),
+                            (z.LaunchOpts(variant=z.VARIANT_ROWVEC, workspace_dev=ws_ptr,
+                                          workspace_bytes=ws_bytes), n),
+                            (z.LaunchOpts(workspace_dev=ws_ptr, workspace_bytes=ws_bytes), 5000)):
+            ws.zero_()
+            out = torch.full((n_use, dim), -7, dtype=TORCH_DT[dtype], device="cuda")
+            z.gather_ex(table, idx_dev, out, opts, n_idx=n_use)
+            torch.cuda.synchronize()
+            assert_same_bits(out, want[:n_use], "plain path")
+            assert not bool(ws.any())  # the workspace was left alone
+        with pytest.raises(z.ZcgError) as e:
+            z.gather_ex(table, idx_dev, out, z.LaunchOpts(workspace_bytes=64))
+        assert e.value.status == -1
     finally:
         table.close()
 
@@ -392,12 +578,17 @@ def test_seeded_random_shapes_knobs_and_offsets():
 
 
 def test_link_probes_give_sane_numbers():
-    rtt = z.measure_host_read_latency(4000)
+    rtt = probe.measure_host_read_latency(4000)
     assert 0.2 < rtt < 50.0  # microseconds per dependent read of mapped host memory
-    assert 5.0 < z.measure_h2d(64 << 20, 3) < 200.0  # GB/s
-    assert 5.0 < z.measure_host_stream_read(64 << 20, 3) < 200.0  # GB/s
-    with pytest.raises(z.ZcgError):
-        z.measure_host_stream_read(1000, 3)  # not a multiple of a page
+    assert 5.0 < probe.measure_h2d(64 << 20, 3) < 200.0  # GB/s
+    assert 5.0 < probe.measure_host_stream_read(64 << 20, 3) < 200.0  # GB/s
+    with pytest.raises(probe.ProbeError):
+        probe.measure_host_stream_read(1000, 3)  # not a multiple of a page
+    a = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    b = torch.zeros_like(a)
+    probe.device_copy(b, a, a.numel() * 4)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
 
 
 @pytest.mark.parametrize("flags", [z.ALLOC_DEFAULT, z.ALLOC_NONCOHERENT])

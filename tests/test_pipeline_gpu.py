@@ -10,6 +10,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 z = pytest.importorskip("paper_2103_03330_amd")
+from paper_2103_03330_amd import probe  # noqa: E402
 
 
 @pytest.mark.parametrize("n_buffers,masked,slow_consumer", [(2, False, False), (2, True, True),
@@ -41,7 +42,7 @@ def test_ring_delivers_every_minibatch(n_buffers, masked, slow_consumer):
                 assert n == want_rows
                 with torch.cuda.stream(consumer):
                     if slow_consumer:
-                        z.synthetic_compute(consumer, 2048, 20000, sink)
+                        probe.synthetic_compute(consumer, 2048, 20000, sink)
                     results.append(buf[:n].clone())
                 pipe.release(slot, consumer)
             pending.append((pipe.submit(idx), idx.size))
@@ -113,7 +114,7 @@ def test_producer_thread_and_consumer_thread():
                     break
                 buf, n = pipe.acquire(slot, stream)
                 with torch.cuda.stream(stream):
-                    z.synthetic_compute(stream, 512, 4000, sink)  # the consumer is the slower side
+                    probe.synthetic_compute(stream, 512, 4000, sink)  # the consumer is the slower side
                     results.append(buf[:n].clone())
                 pipe.release(slot, stream)
             stream.synchronize()
