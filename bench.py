@@ -49,19 +49,45 @@ def nominal_link_gbps():
     return None, "unknown"
 
 
-def read_profile_traffic(name):
-    """Per-row link / HBM bytes measured with rocprofv3 counters, from profiles/<name>."""
+KERNEL_SOURCES = ("zcg_kernels.hip", "zcg_plan.hip")
+PLAN_KEYS = ("variant", "vec_bytes", "log2_group", "iters", "unroll", "half_ends", "blocks", "store_bytes")
+PEAK_NOTE = ("above 1: the peak is the copy engine's measured rate over the same link, the metric's "
+             "denominator, not a ceiling; GPU-issued reads stream slightly faster, and rows a list "
+             "repeats are served from the GPU's L2")
+
+
+def kernel_source_sha():
+    """Fingerprint of the gather kernels and their launch planning: counter summaries under
+    profiles/ carry it, so a summary taken with other kernels is recognised as stale."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2103_03330_amd", "csrc", name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def read_profile_traffic(name, plan):
+    """Per-row link / HBM bytes measured with rocprofv3 counters, from profiles/<name>, or
+    (None, why) when that summary was taken with other kernels or another launch plan than
+    this run's. Lines of the summary: `key = value`; `plan_<field> = n` for every field of
+    PLAN_KEYS and `kernel_source_sha = <hex>` tie it to what was measured."""
     path = os.path.join(ROOT, "profiles", name)
-    out = {}
-    if os.path.exists(path):
-        for line in open(path):
-            if "=" in line and not line.lstrip().startswith("#"):
-                k, v = (s.strip() for s in line.split("=", 1))
-                try:
-                    out[k] = float(v.split()[0])
-                except ValueError:
-                    pass
-    return out
+    if not os.path.exists(path):
+        return None, "no counter summary for this workload under profiles/"
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.lstrip().startswith("#"):
+            k, v = (t.strip() for t in line.split("=", 1))
+            vals[k] = v.split()[0] if v else ""
+    if vals.get("kernel_source_sha") != kernel_source_sha():
+        return None, f"profile stale: {name} was collected with other kernel sources"
+    for k in PLAN_KEYS:
+        if vals.get("plan_" + k) != str(plan[k]):
+            return None, f"profile stale: {name} has plan_{k} = {vals.get('plan_' + k)}, this run {plan[k]}"
+    try:
+        return {k: float(vals[k]) for k in ("link_read_bytes_per_row", "hbm_write_bytes_per_row")}, None
+    except (KeyError, ValueError):
+        return None, f"profile incomplete: {name} lacks the per-row byte figures"
 
 
 def build_workload(z, wl, k, n_batches, flags, max_table_gb):
@@ -84,6 +110,62 @@ def build_workload(z, wl, k, n_batches, flags, max_table_gb):
         g.close()
     return cfg, table, lists, dict(table_s=round(t_table, 2), sampler_s=round(time.time() - t0, 2),
                                    note=note, n_rows=n_rows)
+
+
+def run_side_config(args, z, wl, np, torch, k, link_peak, n_cores):
+    """One of the other single-GPU workloads, measured like the headline one (same step, same
+    clocks) but outside its timed region: wall-clock GB/s over `steps` steps, the kernel alone
+    from HIP events, and the DMA method on the same lists."""
+    cfg, table, lists, info = build_workload(z, wl, k, 8, z.ALLOC_DEFAULT, args.max_table_gb)
+    try:
+        rb = cfg.row_bytes
+        tdt = torch.float32 if cfg.dtype == "f32" else torch.float16
+        idx_dev = [torch.from_numpy(a).cuda() for a in lists]
+        max_n = max(a.size for a in lists)
+        outs = [torch.empty((max_n, cfg.dim), dtype=tdt, device="cuda") for _ in range(2)]
+        stream = torch.cuda.current_stream()
+        plan = z.plan_gather(table, lists[0].size, outs[0])
+        steps = max(5, min(args.steps, 100))
+        for i in range(max(2, min(args.warmup, 10))):
+            z.gather(table, idx_dev[i % 8], outs[i & 1], n_idx=lists[i % 8].size, stream=stream)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0, rows = time.perf_counter(), 0
+        for i in range(steps):
+            ev[i][0].record(stream)
+            z.gather(table, idx_dev[i % 8], outs[i & 1], n_idx=lists[i % 8].size, stream=stream)
+            ev[i][1].record(stream)
+            rows += lists[i % 8].size
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kern_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+        value = rows * rb / wall / 1e9
+        kernel_gbps = rows / steps * rb / (kern_ms * 1e-3) / 1e9
+        staging = z.pinned_alloc(max_n * rb)
+        chunk = max(1024, (4 << 20) // rb)
+        best = 0.0
+        for fn in (lambda b: z.cpu_gather_memcpy(table, lists[b], staging, outs[0], n_cores, stream),
+                   lambda b: z.cpu_gather_memcpy_chunked(table, lists[b], staging, outs[0], chunk, n_cores, stream)):
+            fn(0)
+            torch.cuda.synchronize()
+            t0, r = time.perf_counter(), 0
+            for i in range(max(3, min(steps, 16))):
+                fn(i % 8)
+                torch.cuda.synchronize()
+                r += lists[i % 8].size
+            best = max(best, r * rb / (time.perf_counter() - t0) / 1e9)
+        z.pinned_free(staging)
+        return {"workload": f"{cfg.name}: {cfg.dtype} table {info['n_rows']} x {cfg.dim} ({rb} B rows)",
+                "value": round(value, 3), "unit": "GB/s", "steps": steps,
+                "ms_per_step": round(wall / steps * 1e3, 4), "rows_per_step_avg": round(rows / steps, 1),
+                "fraction_of_link_peak": round(value / link_peak, 4),
+                "kernel_ms_avg": round(kern_ms, 4), "kernel_gbps": round(kernel_gbps, 3),
+                "roofline_frac": round(kernel_gbps / link_peak, 4),
+                "peak_note": PEAK_NOTE if kernel_gbps > link_peak else None,
+                "kernel": z.VARIANT_NAMES[plan["variant"]], "plan": plan,
+                "dma_baseline_gbps": round(best, 3), "zero_copy_speedup": round(value / best, 3)}
+    finally:
+        table.close()
 
 
 def run_sweep(args, z, wl, np, torch, link_peak):
@@ -114,26 +196,38 @@ def run_sweep(args, z, wl, np, torch, link_peak):
             return float(np.median(ms))
 
         useful = idx.size * cfg.row_bytes
-        ms_host = timed(table)
-        # ordered processing: work items walk the table in ascending row order
-        ws_bytes = z.order_workspace_bytes(idx.size)
+        ms_list = timed(table)  # zcg_gather: rows walked in list order
+        # the default call with workspace lent: AUTO walks short rows in ascending table order
+        # when that pays, building the order itself inside the timed call
+        ws_bytes = z.gather_workspace_bytes(idx.size)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-        order = torch.empty(idx.size, dtype=torch.int64, device="cuda")
+        lent = z.LaunchOpts(variant=args.variant, workspace_dev=ws.data_ptr(), workspace_bytes=ws_bytes)
 
-        def ordered(with_sort):
+        def timed_ex(opts, order=None):
+            def call():
+                if order is None:
+                    z.gather_ex(table, idx_dev, out, opts, stream=stream)
+                else:
+                    z.gather_ordered(table, idx_dev, order, out, opts, stream=stream)
+            for _ in range(3):
+                call()
+            torch.cuda.synchronize()
             ms = []
-            for i in range(3 + max(5, min(args.steps, 20))):
+            for _ in range(max(5, min(args.steps, 20))):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
-                if with_sort or i == 0:
-                    z.make_order(idx_dev, cfg.n_rows, order, ws, ws_bytes, stream=stream)
-                z.gather_ordered(table, idx_dev, order, out, stream=stream)
+                call()
                 e1.record(stream)
                 e1.synchronize()
                 ms.append(e0.elapsed_time(e1))
-            return float(np.median(ms[3:]))
+            return float(np.median(ms))
 
-        ms_ord, ms_ord_sort = ordered(False), ordered(True)
+        ms_host = timed_ex(lent)
+        ms_ord = None
+        if cfg.row_bytes <= 128:  # the order built beforehand (what a caller who reuses a list pays)
+            order = torch.empty(idx.size, dtype=torch.int64, device="cuda")
+            z.make_order(idx_dev, cfg.n_rows, order, ws, ws_bytes, stream=stream)
+            ms_ord = timed_ex(None, order)
         del ws
         hbm_t = torch.empty((cfg.n_rows, cfg.dim), dtype=tdt, device="cuda")
         host = table.host_array()
@@ -145,23 +239,38 @@ def run_sweep(args, z, wl, np, torch, link_peak):
         t2.close()
         del hbm_t
         staging = z.pinned_alloc(useful)
-        t0 = time.perf_counter()
-        for _ in range(3):
-            z.cpu_gather_memcpy_chunked(table, idx, staging, out, max(1024, (4 << 20) // cfg.row_bytes),
-                                        wl.default_threads(), stream)
+        dma_runs = {}
+        for name, fn in (("one_shot", lambda: z.cpu_gather_memcpy(table, idx, staging, out,
+                                                                  wl.default_threads(), stream)),
+                         ("chunked", lambda: z.cpu_gather_memcpy_chunked(
+                             table, idx, staging, out, max(1024, (4 << 20) // cfg.row_bytes),
+                             wl.default_threads(), stream))):
+            fn()  # warm-up: first touch of the staging pages
             torch.cuda.synchronize()
-        dma = useful * 3 / (time.perf_counter() - t0) / 1e9
+            t = []
+            for _ in range(5):
+                t0 = time.perf_counter()
+                fn()
+                torch.cuda.synchronize()
+                t.append(time.perf_counter() - t0)
+            dma_runs[name] = useful / float(np.median(t)) / 1e9
+        dma = max(dma_runs.values())
         z.pinned_free(staging)
         lines = -(-cfg.row_bytes // 128)
         points.append({"name": cfg.name, "row_bytes": cfg.row_bytes,
                        "zero_copy_gbps": round(useful / ms_host / 1e6, 2),
                        "fraction_of_link_peak": round(useful / ms_host / 1e6 / link_peak, 4),
                        "rows_per_s": round(idx.size / ms_host * 1e3),
-                       "ordered_gbps": round(useful / ms_ord / 1e6, 2),
-                       "ordered_incl_sort_gbps": round(useful / ms_ord_sort / 1e6, 2),
+                       "call": "zcg_gather_ex, variant AUTO, workspace lent",
+                       "list_order_gbps": round(useful / ms_list / 1e6, 2),
+                       "order_built_beforehand_gbps": round(useful / ms_ord / 1e6, 2) if ms_ord else None,
+                       "peak_note": PEAK_NOTE if useful / ms_host / 1e6 > link_peak else None,
                        "useful_over_line_bytes": round(cfg.row_bytes / (lines * 128), 3),
                        "hbm_resident_gbps": round(useful / ms_hbm / 1e6, 1),
-                       "dma_chunked_gbps": round(dma, 2)})
+                       "dma_baseline_gbps": round(dma, 2),
+                       "dma_one_shot_gbps": round(dma_runs["one_shot"], 2),
+                       "dma_chunked_gbps": round(dma_runs["chunked"], 2),
+                       "zero_copy_speedup": round(useful / ms_host / 1e6 / dma, 3)})
         table.close()
         print(f"# {points[-1]}", file=sys.stderr, flush=True)
     return points
@@ -648,6 +757,8 @@ def main():
     ap.add_argument("--pipeline-mode", default="all",
                     choices=["all", "serial", "nomask", "mask8", "mask16", "mask24", "threads"],
                     help="config 8: run one mode only (for kernel-trace profiles)")
+    ap.add_argument("--no-side-configs", action="store_true",
+                    help="default run: skip the configs 1 and 3 legs that follow the headline workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy, as the known-size reference for counters")
     args = ap.parse_args()
@@ -739,9 +850,9 @@ def main():
         return lists[b].size
 
     if args.calibrate_copy:
-        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
         b = torch.empty_like(a)
-        b.copy_(a)
+        probe.device_copy(b, a, a.numel(), stream)  # zcgp_k_copy: reads and writes 256 MiB each
         torch.cuda.synchronize()
 
     for i in range(args.warmup):
@@ -804,12 +915,13 @@ def main():
         t_hbm.close()
         del hbm_t
 
-    prof = read_profile_traffic(f"gather_cfg{args.config}_counters.txt")
+    prof, traffic_note = read_profile_traffic(f"gather_cfg{args.config}_counters.txt", plan)
     traffic = None
-    if "link_read_bytes_per_row" in prof:
+    if prof:
         traffic = {"link_read_bytes": round(prof["link_read_bytes_per_row"] * avg_rows),
-                   "hbm_write_bytes": round(prof.get("hbm_write_bytes_per_row", rb) * avg_rows),
-                   "source": f"profiles/gather_cfg{args.config}_counters.txt (rocprofv3 --pmc)"}
+                   "hbm_write_bytes": round(prof["hbm_write_bytes_per_row"] * avg_rows),
+                   "source": f"profiles/gather_cfg{args.config}_counters.txt (rocprofv3 --pmc, "
+                             f"same kernel sources and launch plan as this run)"}
 
     from paper_2103_03330_amd import link_model
     model_bytes = float(np.mean([link_model.link_bytes_per_row(rb, a, table.device_ptr,
@@ -852,6 +964,8 @@ def main():
                                  "max": round(float(per_step_gbps.max()), 2)},
         "roofline": {"bound": "host_link", "achieved": round(achieved, 3), "peak": round(link_peak, 2),
                      "unit": "GB/s", "frac": round(achieved / link_peak, 4), "traffic": traffic,
+                     "traffic_note": traffic_note, "kernel_source_sha": kernel_source_sha(),
+                     "peak_note": PEAK_NOTE if achieved > link_peak else None,
                      "traffic_model": {"link_read_bytes": round(model_bytes * avg_rows),
                                        "link_bytes_per_row": round(model_bytes, 1),
                                        "useful_over_link": round(rb / model_bytes, 4),
@@ -928,8 +1042,12 @@ def main():
                                             f"pageable destination, no transfer to the GPU",
                                   "one_thread_gbps": round(o_one, 3),
                                   "cpu": _cpu_model()}
-    print(json.dumps(result))
     table.close()
+    if args.config == 2 and not args.no_baselines and not args.no_side_configs:
+        # the other workloads that set up in about a second (51 MB and 561 MB tables), same clocks
+        result["other_configs"] = {f"cfg{k}": run_side_config(args, z, wl, np, torch, k, link_peak, n_cores)
+                                   for k in (1, 3)}
+    print(json.dumps(result))
 
 
 def _cpu_model():

@@ -62,8 +62,8 @@ extern "C" {
                                  else ALIGNED, or HALFLINE for host-resident rows of more
                                  than a line (also for multi-pass whole-line rows off
                                  the 256-byte pair grid). With workspace lent through
-                                 zcg_launch_opts, long lists of host-resident rows of at
-                                 most a line are walked in ascending table order.       */
+                                 zcg_launch_opts, long dense lists of host-resident rows
+                                 of at most a line are walked in ascending table order.  */
 #define ZCG_VARIANT_NAIVE 1   /* one element per lane over the flat output, no alignment
                                  care: the paper's baseline kernel (Section 4.1.2 (c))  */
 #define ZCG_VARIANT_ROWVEC 2  /* a lane group per row, widest vector, loads start at the
@@ -116,13 +116,15 @@ typedef struct zcg_launch_opts {
                       the call may overwrite while it runs on its stream (free to reuse
                       once the stream has passed the call; two calls that overlap in
                       time need two workspaces). With variant AUTO and at least
-                      zcg_gather_workspace_bytes(n_idx) bytes, zcg_gather_ex walks long
-                      lists (131,072 entries or more) of host-resident rows of at most
-                      128 bytes in ascending table order: it builds the order in the
-                      workspace with a few kernels of its own on the same stream, then
-                      gathers through it. The result is the same bit for bit; rows that
-                      share a line or a 256-byte pair of lines then share a link
-                      request. Ignored where that does not pay or does not fit.       */
+                      zcg_gather_workspace_bytes(n_idx) bytes, zcg_gather_ex walks lists
+                      of host-resident rows of at most 128 bytes in ascending table
+                      order where that pays: it builds the order in the workspace with
+                      a few kernels of its own on the same stream (about 0.1 ms), then
+                      gathers through it. The result is the same bit for bit; listed
+                      rows that share a line or a 256-byte pair of lines then share a
+                      link request, so the walk pays for long lists that are dense in
+                      their table (decided from n_idx, n_rows and the row size).
+                      Ignored otherwise, and by every forced variant.                   */
   int64_t workspace_bytes; /* size of workspace_dev in bytes (0 with a null pointer)       */
 } zcg_launch_opts;
 
@@ -336,8 +338,9 @@ int zcg_device_cu_count(int device, int* n_cus);
  *                   zcg_stream_create_cu_mask); NULL = the pipeline creates its own
  * The pipeline owns, per buffer, a pinned staging area and a device copy of the
  * index list (max_rows int64 each). For host-resident tables with rows of at
- * most 128 bytes it also owns the memory of zcg_make_order and gathers every
- * list in ascending table order (same result, fewer link requests). Threads: ONE producer thread (submit,
+ * most 128 bytes it also owns the memory of zcg_make_order and gathers lists
+ * that are long and dense enough in the table in ascending table order (same
+ * result, fewer link requests). Threads: ONE producer thread (submit,
  * submit_wait, finish) and ONE consumer thread (next, acquire, release) may run
  * at the same time; they may also be the same thread. The consumer takes slot
  * numbers either from submit's result or from zcg_pipeline_next, not from both.

@@ -473,3 +473,4 @@ def make_order(idx_dev, n_rows: int, order_dev, workspace_dev, workspace_bytes: 
     rc = load_library().zcg_make_order(_ptr(idx_dev), _n_idx(idx_dev, n_idx), n_rows, _ptr(order_dev),
                                        _ptr(workspace_dev), workspace_bytes, _stream(stream))
     _check(rc, "zcg_make_order")
+

@@ -4,6 +4,7 @@
 // baseline in zcg_cpu_baseline.hip, the pipeline in zcg_pipeline.hip.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <mutex>
 #include <new>
 #include <unordered_set>
@@ -76,6 +77,28 @@ int zcg_fail_hip(hipError_t e) {
   t_last_hip = (int)e;
   (void)hipGetLastError();  // do not leave a sticky error for the caller's next HIP call
   return ZCG_EHIP;
+}
+
+// Rows of at most one line over the host link are bound by the link's request rate (about 320
+// requests per microsecond); walked in ascending table order, listed rows that share a line or
+// a 256-byte pair of lines share a request. With lambda listed rows per pair on average, a
+// fraction 1 - (1 - exp(-lambda)) / lambda of the requests goes away; measured, about 0.6 of
+// that is realised (1 M entries over 10 M rows: 32-byte rows 11.1 -> 14.5 GB/s, 64-byte rows
+// 21.5 -> 25.0, 128-byte rows 41.1 -> 46.0). Building the order is launch-bound: about 20 us
+// plus 25 us per 8-bit digit of the row number. A caller that lends workspace gets the ordered
+// walk from AUTO whenever the saving clearly exceeds that cost -- long lists that are dense in
+// their table -- and the plain walk otherwise (262,144 entries over 10 M rows: ordering would
+// save 4 % and cost 10 %).
+bool zcg_order_pays(const zcg_table* t, int64_t n_idx) {
+  if (!t->host_resident || t->row_bytes > 128 || n_idx < 32768 || n_idx > (int64_t)UINT32_MAX)
+    return false;
+  const double lambda = (double)n_idx * 256.0 / ((double)t->row_bytes * (double)t->n_rows);
+  const double shared = 1.0 - (1.0 - std::exp(-lambda)) / lambda;
+  const double saved_us = 0.6 * shared * (double)n_idx / 320.0;
+  int bits = 1;
+  while (bits < 63 && ((int64_t)1 << bits) < t->n_rows) ++bits;
+  const double build_us = 20.0 + 25.0 * (double)((bits + 7) / 8);
+  return saved_us > 1.25 * build_us;
 }
 
 extern "C" {
@@ -223,17 +246,12 @@ int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
                        t->host_resident, false, opts, plan);
 }
 
-// Rows of at most one line over the host link are bound by the link's request rate; walked in
-// ascending table order, rows that share a line or a 256-byte pair of lines share a request
-// (measured with the order built on the clock: +25 % on 32-byte rows, +5...12 % on 64- and
-// 128-byte rows from ~128 k list entries on). A caller that lends workspace gets this from AUTO.
 static bool wants_order(const zcg_table* t, int64_t n_idx, const zcg_launch_opts* opts) {
   if (!opts || !opts->workspace_dev || opts->variant != ZCG_VARIANT_AUTO) return false;
-  if (!t->host_resident || t->row_bytes > 128 || n_idx < 131072 || n_idx > (int64_t)UINT32_MAX)
-    return false;
   if ((uintptr_t)opts->workspace_dev % 256) return false;
   const int64_t order_bytes = (n_idx * 8 + 255) / 256 * 256;
-  return opts->workspace_bytes >= order_bytes + zcg_order_scratch_bytes(n_idx);
+  if (opts->workspace_bytes < order_bytes + zcg_order_scratch_bytes(n_idx)) return false;
+  return zcg_order_pays(t, n_idx);
 }
 
 static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,

@@ -27,6 +27,9 @@ struct zcg_table {
 // zcg_api.hip
 bool zcg_is_live(const zcg_table* t);
 int zcg_fail_hip(hipError_t e);  // records e for zcg_last_hip_error, returns ZCG_EHIP
+// whether walking this list in ascending table order saves more link time than building the
+// order costs (short host-resident rows, long lists that are dense in the table)
+bool zcg_order_pays(const zcg_table* t, int64_t n_idx);
 
 // zcg_plan.hip
 int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t out_addr,

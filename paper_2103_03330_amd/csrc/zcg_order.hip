@@ -15,8 +15,7 @@
 //             time with ballots, so the pass is stable and its result does not
 //             depend on scheduling.
 // No kernel waits for another block, nothing is cleared with a memory-set, and all
-// temporary memory is the caller's (or the static array of the allocation-free
-// entry point): the whole build is a chain of plain kernel launches on one stream.
+// temporary memory is the caller's: the whole build is a chain of plain kernel launches on one stream.
 // Between passes an element travels as (32-bit key, 32-bit list position); the
 // output array doubles as the second buffer of the ping-pong. Tables of 2^32 rows
 // or more carry the position only and look the key up again in the list.

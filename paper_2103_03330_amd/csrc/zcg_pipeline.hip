@@ -26,8 +26,9 @@ struct zcg_pipeline {
   bool own_stream = false;
   // Rows of at most one line over the host link are bound by the request rate; walked in
   // ascending table order, neighbouring rows share lines and pairs of lines (measured +12 %
-  // on 128-byte rows, +30 % on 32-byte rows, order build included). The pipeline owns the
-  // memory the order builder needs, so it does this by itself.
+  // on 128-byte rows, +30 % on 32-byte rows, order build included, for lists that are dense in
+  // the table). The pipeline owns the memory the order builder needs, so it does this by
+  // itself for every minibatch where zcg_order_pays says so.
   bool sorts = false;
   int64_t sort_ws_bytes = 0;
   hipStream_t gather_stream = nullptr;
@@ -128,7 +129,7 @@ int submit_impl(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx, int tim
     std::memcpy(s.idx_pinned, idx_host, (size_t)n_idx * sizeof(int64_t));
     e = hipMemcpyAsync(s.idx_dev, s.idx_pinned, (size_t)n_idx * sizeof(int64_t),
                        hipMemcpyHostToDevice, p->gather_stream);
-    if (e == hipSuccess && p->sorts) {
+    if (e == hipSuccess && p->sorts && zcg_order_pays(p->table, n_idx)) {
       rc = zcg_make_order(s.idx_dev, n_idx, p->table->n_rows, s.order, s.sort_ws, p->sort_ws_bytes,
                           p->gather_stream);
       if (rc == ZCG_OK)

@@ -182,8 +182,9 @@ def test_bounded_waits_time_out():
 
 
 def test_ring_sorts_short_rows_by_itself():
-    """Tables with rows of at most a line are gathered in ascending table order inside the ring;
-    the delivered rows are still in list order."""
+    """Tables with rows of at most a line: lists that are long and dense enough in the table
+    (here the 150,001-entry ones) are gathered in ascending table order inside the ring, short
+    ones in list order; the delivered rows are in list order either way."""
     if not torch.cuda.is_available():
         pytest.fail("GPU tests need a GPU")
     torch.cuda.set_device(0)
@@ -191,9 +192,9 @@ def test_ring_sorts_short_rows_by_itself():
         n_rows = 200_000
         table = z.alloc_table(n_rows, dim, dtype)
         wl.fill_table_ptr(table.host_ptr, n_rows, dim, dtype, seed=47 + dim)
-        lists = [wl.uniform_indices(n, n_rows, seed=n) for n in (70_001, 1, 33_333, 70_001)]
-        bufs = [torch.zeros((70_001, dim), dtype=tdt, device="cuda") for _ in range(2)]
-        pipe = z.pipeline_create(table, 70_001, bufs)
+        lists = [wl.uniform_indices(n, n_rows, seed=n) for n in (150_001, 1, 33_333, 150_001)]
+        bufs = [torch.zeros((150_001, dim), dtype=tdt, device="cuda") for _ in range(2)]
+        pipe = z.pipeline_create(table, 150_001, bufs)
         try:
             for idx in lists:
                 slot = pipe.submit(idx)
