@@ -268,6 +268,24 @@ int zcg_order_workspace_bytes(int64_t n_idx, int64_t* bytes);
 int zcg_make_order(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_t* order_dev,
                    void* workspace_dev, int64_t workspace_bytes, void* stream);
 
+/*
+ * zcg_make_order for callers that cannot allocate or lend device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same order, same kernels; the temporary memory is a static device array inside
+ * the library (8.5 MiB on every GPU the library runs on, held until the process
+ * ends) instead of a workspace argument. The call allocates nothing.
+ *   n_idx <= ZCG_STATIC_ORDER_MAX_IDX (ZCG_EINVAL beyond); other arguments and
+ *   errors as zcg_make_order. Works on the current device.
+ * Every call on one GPU shares that GPU's array: two calls that overlap in time
+ * on one GPU (different streams, no ordering between them) race and give a wrong
+ * order; calls on one stream, or ordered by events, are fine. Nothing in the array
+ * has to be cleared between calls. The first call on a device looks the array's
+ * address up once; make that call outside stream capture.
+ */
+#define ZCG_STATIC_ORDER_MAX_IDX 1048576
+int zcg_make_order_static(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_t* order_dev,
+                          void* stream);
+
 /* Bytes of zcg_launch_opts.workspace_dev that let zcg_gather_ex order a list of n_idx
  * entries by itself: the order (8 bytes per entry) plus zcg_order_workspace_bytes. */
 int zcg_gather_workspace_bytes(int64_t n_idx, int64_t* bytes);

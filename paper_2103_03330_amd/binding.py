@@ -41,6 +41,7 @@ EXPORTS = [
     "zcg_pipeline_finish", "zcg_pipeline_next", "zcg_pipeline_acquire",
     "zcg_pipeline_release", "zcg_pipeline_destroy", "zcg_gather_ordered",
     "zcg_order_workspace_bytes", "zcg_make_order", "zcg_table_view", "zcg_gather_workspace_bytes",
+    "zcg_make_order_static",
 ]
 
 
@@ -124,6 +125,7 @@ def load_library() -> ctypes.CDLL:
         "zcg_gather_ordered": (i32, [vp, vp, vp, i64, vp, vp, ctypes.POINTER(LaunchOpts)]),
         "zcg_order_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
         "zcg_make_order": (i32, [vp, i64, i64, vp, vp, i64, vp]),
+        "zcg_make_order_static": (i32, [vp, i64, i64, vp, vp]),
         "zcg_table_view": (i32, [vp, i64, i64, i64, i32, pvp]),
         "zcg_gather_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
     }
@@ -474,3 +476,12 @@ def make_order(idx_dev, n_rows: int, order_dev, workspace_dev, workspace_bytes: 
                                        _ptr(workspace_dev), workspace_bytes, _stream(stream))
     _check(rc, "zcg_make_order")
 
+
+STATIC_ORDER_MAX_IDX = 1 << 20
+
+
+def make_order_static(idx_dev, n_rows: int, order_dev, n_idx: Optional[int] = None, stream=None) -> None:
+    _check_idx_tensor(idx_dev)
+    rc = load_library().zcg_make_order_static(_ptr(idx_dev), _n_idx(idx_dev, n_idx), n_rows,
+                                              _ptr(order_dev), _stream(stream))
+    _check(rc, "zcg_make_order_static")

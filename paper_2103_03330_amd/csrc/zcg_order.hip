@@ -15,13 +15,23 @@
 //             time with ballots, so the pass is stable and its result does not
 //             depend on scheduling.
 // No kernel waits for another block, nothing is cleared with a memory-set, and all
-// temporary memory is the caller's: the whole build is a chain of plain kernel launches on one stream.
+// temporary memory is the caller's (or the static array of the allocation-free
+// entry point): the whole build is a chain of plain kernel launches on one stream.
 // Between passes an element travels as (32-bit key, 32-bit list position); the
 // output array doubles as the second buffer of the ping-pong. Tables of 2^32 rows
 // or more carry the position only and look the key up again in the list.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "zcg_internal.h"
+
+// Temporary memory of zcg_make_order_static: one array per GPU the library runs on, held until
+// the process ends. In host code this name is only a handle for hipGetSymbolAddress, never an
+// address to pass on.
+constexpr int64_t kStaticMaxIdx = ZCG_STATIC_ORDER_MAX_IDX;
+constexpr int64_t kStaticScratchBytes = kStaticMaxIdx * 8 + (512 << 10);
+static __device__ __align__(256) unsigned char zcg_order_static_scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -294,7 +304,49 @@ hipError_t zcg_order_launch(const int64_t* idx, int64_t n, int64_t n_rows, int64
   return hipSuccess;
 }
 
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[kMaxDevices] = {};  // device address of the static array, per device
+
+// The array's address on the current device, looked up once per device.
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(zcg_order_static_scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return hipSuccess;
+}
+
+}  // namespace
+
 extern "C" {
+
+int zcg_make_order_static(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_t* order_dev,
+                          void* stream) {
+  if (n_idx < 0 || n_rows < 1 || n_idx > kStaticMaxIdx) return ZCG_EINVAL;
+  if (n_idx == 0) return ZCG_OK;
+  if (!idx_dev || !order_dev) return ZCG_EINVAL;
+  if (((uintptr_t)idx_dev | (uintptr_t)order_dev) % 8) return ZCG_EALIGN;
+  if (zcg_order_scratch_bytes(n_idx) > kStaticScratchBytes) return ZCG_EINVAL;
+  void* scratch = nullptr;
+  hipError_t e = static_scratch(&scratch);
+  if (e != hipSuccess) return zcg_fail_hip(e);
+  // nothing in the array has to start at zero: every count, prefix and buffer entry a pass
+  // reads was written earlier in the same call
+  e = zcg_order_launch(idx_dev, n_idx, n_rows, order_dev, scratch, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
+}
 
 int zcg_order_workspace_bytes(int64_t n_idx, int64_t* bytes) {
   if (n_idx < 0 || !bytes) return ZCG_EINVAL;
