@@ -692,6 +692,59 @@ def run_request_blocks(args, z, wl, np, torch):
     return pts
 
 
+def run_request_sequence(args, z, wl, np, torch):
+    """A fixed sequence of gathers, each configuration launched 4 times in a row (the first is a
+    warm-up), for matching rocprofv3 per-dispatch counters and kernel-trace durations to
+    configurations by order: the kernels of config 2 at full and at capped grid sizes (how many
+    reads must be in flight), and random rows of 128 ... 512 bytes on and off the 256-byte grid
+    (what the link counts as one request). Prints the labels in launch order."""
+    labels, reps = [], 4
+
+    def run(label, table, idx_dev, out, opts, n, rb):
+        for _ in range(reps):
+            z.gather_ex(table, idx_dev, out, opts, n_idx=n)
+            torch.cuda.synchronize()
+        labels.append({"label": label, "n_idx": int(n), "row_bytes": int(rb), "launches": reps})
+
+    cfg = wl.config(2)
+    table = z.alloc_table(cfg.n_rows, cfg.dim, cfg.dtype)
+    wl.fill_table_ptr(table.host_ptr, cfg.n_rows, cfg.dim, cfg.dtype, cfg.seed)
+    idx = wl.index_lists(cfg)[0]
+    idx_dev = torch.from_numpy(idx).cuda()
+    out = torch.empty((idx.size, cfg.dim), dtype=torch.float32, device="cuda")
+    seq = [("cfg2 rowvec", dict(variant=z.VARIANT_ROWVEC)), ("cfg2 aligned", dict(variant=z.VARIANT_ALIGNED)),
+           ("cfg2 half-all", dict(variant=z.VARIANT_HALFLINE, half_ends=1)),
+           ("cfg2 half-lone", dict(variant=z.VARIANT_HALFLINE, half_ends=2))]
+    seq += [(f"cfg2 half-lone {b} blocks", dict(variant=z.VARIANT_HALFLINE, half_ends=2, max_blocks=b))
+            for b in (8, 16, 32, 48, 64, 96, 128, 256, 1024, 4096)]
+    seq += [(f"cfg2 aligned {b} blocks", dict(variant=z.VARIANT_ALIGNED, max_blocks=b)) for b in (16, 32, 64, 128, 256)]
+    for name, o in seq:
+        run(name, table, idx_dev, out, z.LaunchOpts(**o), idx.size, cfg.row_bytes)
+    table.close()
+    n_rows, n_idx = 4_000_000, 400_000
+    idx_dev = torch.from_numpy(wl.uniform_indices(n_idx, n_rows, seed=5)).cuda()
+    for dim in (128, 64, 32, 16):
+        rb = dim * 4
+        base = z.alloc_table(n_rows + 2, dim, "f32")
+        out = torch.empty((n_idx, dim), dtype=torch.float32, device="cuda")
+        wide = rb > 128
+        for off in ((0, 128) if rb >= 128 else (0,)):
+            view = z.table_view(base, off, n_rows, dim, "f32")  # stays host-resident
+            o = z.LaunchOpts(variant=z.VARIANT_ROWVEC, unroll=2, max_blocks=2048 if wide else 8192,
+                             vec_bytes=8 if wide else 16, group_lanes=64 if wide else 16)
+            run(f"rows {rb} B base+{off}", view, idx_dev, out, o, n_idx, rb)
+            if off == 0 and rb in (128, 256):
+                for b in (8, 16, 32, 64, 128, 256):
+                    o = z.LaunchOpts(variant=z.VARIANT_ROWVEC, unroll=2, max_blocks=b,
+                                     vec_bytes=8 if wide else 16, group_lanes=64)
+                    run(f"rows {rb} B base+0 {b} blocks", view, idx_dev, out, o, n_idx, rb)
+            view.close()
+        if rb == 64:  # the same rows through one 64-byte scalar read each
+            run("rows 64 B base+0 scalar reads", base, idx_dev, out, z.LaunchOpts(variant=z.VARIANT_HALFLINE), n_idx, rb)
+        base.close()
+    return labels
+
+
 def run_list_length(args, z, wl, np, torch, link_peak):
     """Gather time against list length for rows of 512 B ... 1 MiB: where the launch and the first
     round trip dominate, where the link fills, and what giving several wavefronts to one long
@@ -744,7 +797,8 @@ def main():
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep; "
                          "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning; "
-                         "8 = producer/consumer pipeline; 9 = list-length sweep")
+                         "8 = producer/consumer pipeline; 9 = list-length sweep; "
+                         "10 = fixed launch sequence for the link request counters")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
     ap.add_argument("--variant", type=int, default=0,
                     help="force a kernel (ablation; configs 1-5): 1 naive, 2 rowvec, 3 aligned, 4 halfline")
@@ -783,6 +837,9 @@ def main():
     n_cores = wl.default_threads()
     n_batches = args.batches or (50 if args.config == 4 else 16)
 
+    if args.config == 10:  # no probes here: the profiler should see the gather kernels only
+        print(json.dumps({"request_sequence": run_request_sequence(args, z, wl, np, torch)}))
+        return
     link_peak = probe.measure_h2d(1 << 30, 10)
     nominal, link_name = nominal_link_gbps()
 
@@ -973,7 +1030,7 @@ def main():
                                        "what": "whole 128 B lines spanned by each row, 64 B for row ends "
                                                "taken through the scalar cache (half-line kernel); "
                                                "requests: 256 B aligned line pairs, lone lines and "
-                                               "64 B reads count one each (inferred from timing)"},
+                                               "64 B reads count one each (profiles/link_request_model.txt)"},
                      "kernel_ms_avg": round(avg_kernel_ms, 4),
                      "hbm_side": {"bytes_per_row": rb + 8, "achieved_gbps": round(achieved * (rb + 8) / rb, 1),
                                   "peak_gbps": 8000.0, "frac": round(achieved * (rb + 8) / rb / 8000.0, 5),
@@ -981,9 +1038,10 @@ def main():
                                           "which is why the host link is the roofline of this path"},
                      "peak_is": "measured pinned hipMemcpyAsync host->device (1 GiB, median of 10)",
                      "algorithmic_bytes_per_row": rb,
-                     "ceiling_note": "vector loads move whole 128 B lines and the link serves ~320 M "
-                                     "requests/s: a row costs its lines (or half lines at lone row "
-                                     "ends) in bytes and its line pairs in requests"},
+                     "ceiling_note": "vector loads move whole 128 B lines and the link serves ~322 M "
+                                     "requests/s (about 570 in flight fill it): a row costs its lines "
+                                     "(or half lines at lone row ends) in bytes and its line pairs in "
+                                     "requests"},
         "setup_s": build_info,
     }
 

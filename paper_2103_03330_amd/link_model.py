@@ -5,7 +5,11 @@ host memory costs every 128-byte line it touches, whole; a wave-uniform load
 through the scalar data cache costs one 64-byte half line. The model counts,
 per row, the lines its byte range spans (and for the half-line kernel the ends
 that are fetched as half lines), and the requests these make when lines of one
-256-byte aligned pair travel together. Lines shared by different rows of one list are
+256-byte aligned pair travel together. The request rules rest on counters plus
+time (profiles/link_request_model.txt): the link serves at most about 322-337 M
+read requests per second (about 570 in flight fill it); rows of 256 bytes on and
+off the 256-byte grid show identical L2-side read counts but 225 against 161 M
+rows/s, the second being exactly two requests per row at the request limit. Lines shared by different rows of one list are
 counted once per row: the hardware saves a little more when such rows are
 processed close together.
 """
@@ -58,10 +62,11 @@ def link_bytes_per_row(row_bytes: int, idx: np.ndarray, base_addr: int = 0,
 
 def link_requests_per_row(row_bytes: int, idx: np.ndarray, base_addr: int = 0,
                           half_ends: int = 0) -> float:
-    """Mean read requests per listed row as the link sees them. Inferred from timing, not from a
-    counter: two lines of one 256-byte aligned pair asked for together travel as one request,
-    a lone line is one request, a 64-byte scalar read is one request, and the link serves about
-    320 M requests/s whatever their size (up to its byte rate)."""
+    """Mean read requests per listed row as the link sees them: two lines of one 256-byte aligned
+    pair asked for together travel as one request, a lone line is one request, a 64-byte scalar
+    read is one request, and the link serves about 322-337 M requests/s whatever their size (up
+    to its byte rate). The L2's own counters see lines, not pairs; the pairing is established by
+    equal counters and unequal times of on-grid and off-grid rows."""
     s, e, vs, ve, head, tail = _split(row_bytes, idx, base_addr, half_ends)
     pairs = np.where(ve > vs, (ve - 1) // (2 * LINE) - vs // (2 * LINE) + 1, 0)
     return float(np.mean(pairs + head.astype(np.int64) + tail.astype(np.int64)))
