@@ -170,64 +170,55 @@ def run_side_config(args, z, wl, np, torch, k, link_peak, n_cores):
 
 def run_sweep(args, z, wl, np, torch, link_peak):
     """Config 5: 10 M rows x dim in {16,64,256,1024}, fp16 and fp32, 1 M uniform indices per call;
-    host-resident zero-copy vs the same table copied to HBM. One JSON line with all points."""
+    host-resident zero-copy vs the same table copied to HBM, and the DMA method. Every leg cycles
+    over 8 distinct lists, as training would (no leg sees the same rows twice in a row, so neither
+    the GPU's L2 nor the CPU's last-level cache is warmed by the previous call). One JSON line."""
     points = []
+    n_lists = 8
     for cfg in wl.sweep_configs():
+        if args.only_point and cfg.name != args.only_point:
+            continue
         table = z.alloc_table(cfg.n_rows, cfg.dim, cfg.dtype)
         wl.fill_table_ptr(table.host_ptr, cfg.n_rows, cfg.dim, cfg.dtype, cfg.seed)
-        idx = wl.index_lists(cfg)[0]
-        idx_dev = torch.from_numpy(idx).cuda()
+        lists = [wl.uniform_indices(cfg.n_idx, cfg.n_rows, (cfg.seed ^ 0x1D) + b) for b in range(n_lists)]
+        idx_dev = [torch.from_numpy(a).cuda() for a in lists]
+        n = cfg.n_idx
         tdt = torch.float32 if cfg.dtype == "f32" else torch.float16
-        out = torch.empty((idx.size, cfg.dim), dtype=tdt, device="cuda")
+        out = torch.empty((n, cfg.dim), dtype=tdt, device="cuda")
         stream = torch.cuda.current_stream()
+        reps = max(8, min(args.steps, 24))
 
-        def timed(t):
-            for _ in range(3):
-                z.gather_variant(t, idx_dev, out, args.variant, stream=stream)
+        def timed(call):
+            """Median time of call(b) over `reps` calls that cycle through the lists."""
+            for b in range(3):
+                call(b)
             torch.cuda.synchronize()
             ms = []
-            for _ in range(max(5, min(args.steps, 20))):
+            for i in range(reps):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(stream)
-                z.gather_variant(t, idx_dev, out, args.variant, stream=stream)
+                call((3 + i) % n_lists)
                 e1.record(stream)
                 e1.synchronize()
                 ms.append(e0.elapsed_time(e1))
             return float(np.median(ms))
 
-        useful = idx.size * cfg.row_bytes
-        ms_list = timed(table)  # zcg_gather: rows walked in list order
+        useful = n * cfg.row_bytes
+        # zcg_gather: rows walked in list order
+        ms_list = timed(lambda b: z.gather_variant(table, idx_dev[b], out, args.variant, stream=stream))
         # the default call with workspace lent: AUTO walks short rows in ascending table order
         # when that pays, building the order itself inside the timed call
-        ws_bytes = z.gather_workspace_bytes(idx.size)
+        ws_bytes = z.gather_workspace_bytes(n)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
         lent = z.LaunchOpts(variant=args.variant, workspace_dev=ws.data_ptr(), workspace_bytes=ws_bytes)
-
-        def timed_ex(opts, order=None):
-            def call():
-                if order is None:
-                    z.gather_ex(table, idx_dev, out, opts, stream=stream)
-                else:
-                    z.gather_ordered(table, idx_dev, order, out, opts, stream=stream)
-            for _ in range(3):
-                call()
-            torch.cuda.synchronize()
-            ms = []
-            for _ in range(max(5, min(args.steps, 20))):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                call()
-                e1.record(stream)
-                e1.synchronize()
-                ms.append(e0.elapsed_time(e1))
-            return float(np.median(ms))
-
-        ms_host = timed_ex(lent)
+        ms_host = timed(lambda b: z.gather_ex(table, idx_dev[b], out, lent, stream=stream))
         ms_ord = None
-        if cfg.row_bytes <= 128:  # the order built beforehand (what a caller who reuses a list pays)
-            order = torch.empty(idx.size, dtype=torch.int64, device="cuda")
-            z.make_order(idx_dev, cfg.n_rows, order, ws, ws_bytes, stream=stream)
-            ms_ord = timed_ex(None, order)
+        if cfg.row_bytes <= 128:  # the orders built beforehand (what a caller who reuses lists pays)
+            orders = [torch.empty(n, dtype=torch.int64, device="cuda") for _ in range(n_lists)]
+            for b in range(n_lists):
+                z.make_order(idx_dev[b], cfg.n_rows, orders[b], ws, ws_bytes, stream=stream)
+            ms_ord = timed(lambda b: z.gather_ordered(table, idx_dev[b], orders[b], out, stream=stream))
+            del orders
         del ws
         hbm_t = torch.empty((cfg.n_rows, cfg.dim), dtype=tdt, device="cuda")
         host = table.host_array()
@@ -235,22 +226,22 @@ def run_sweep(args, z, wl, np, torch, link_peak):
         for lo in range(0, cfg.n_rows, step):
             hbm_t[lo:lo + step].copy_(torch.from_numpy(host[lo:lo + step]))
         t2 = z.table_from_device(hbm_t, cfg.n_rows, cfg.dim, cfg.dtype)
-        ms_hbm = timed(t2)
+        ms_hbm = timed(lambda b: z.gather_variant(t2, idx_dev[b], out, args.variant, stream=stream))
         t2.close()
         del hbm_t
         staging = z.pinned_alloc(useful)
         dma_runs = {}
-        for name, fn in (("one_shot", lambda: z.cpu_gather_memcpy(table, idx, staging, out,
-                                                                  wl.default_threads(), stream)),
-                         ("chunked", lambda: z.cpu_gather_memcpy_chunked(
-                             table, idx, staging, out, max(1024, (4 << 20) // cfg.row_bytes),
+        for name, fn in (("one_shot", lambda b: z.cpu_gather_memcpy(table, lists[b], staging, out,
+                                                                   wl.default_threads(), stream)),
+                         ("chunked", lambda b: z.cpu_gather_memcpy_chunked(
+                             table, lists[b], staging, out, max(1024, (4 << 20) // cfg.row_bytes),
                              wl.default_threads(), stream))):
-            fn()  # warm-up: first touch of the staging pages
+            fn(0)  # warm-up: first touch of the staging pages
             torch.cuda.synchronize()
             t = []
-            for _ in range(5):
+            for i in range(n_lists):
                 t0 = time.perf_counter()
-                fn()
+                fn((i + 1) % n_lists)
                 torch.cuda.synchronize()
                 t.append(time.perf_counter() - t0)
             dma_runs[name] = useful / float(np.median(t)) / 1e9
@@ -260,7 +251,7 @@ def run_sweep(args, z, wl, np, torch, link_peak):
         points.append({"name": cfg.name, "row_bytes": cfg.row_bytes,
                        "zero_copy_gbps": round(useful / ms_host / 1e6, 2),
                        "fraction_of_link_peak": round(useful / ms_host / 1e6 / link_peak, 4),
-                       "rows_per_s": round(idx.size / ms_host * 1e3),
+                       "rows_per_s": round(n / ms_host * 1e3),
                        "call": "zcg_gather_ex, variant AUTO, workspace lent",
                        "list_order_gbps": round(useful / ms_list / 1e6, 2),
                        "order_built_beforehand_gbps": round(useful / ms_ord / 1e6, 2) if ms_ord else None,
@@ -811,6 +802,8 @@ def main():
     ap.add_argument("--pipeline-mode", default="all",
                     choices=["all", "serial", "nomask", "mask8", "mask16", "mask24", "threads"],
                     help="config 8: run one mode only (for kernel-trace profiles)")
+    ap.add_argument("--only-point", default="",
+                    help="config 5: run one point only, by name (e.g. cfg5_f16_d16; for kernel-trace profiles)")
     ap.add_argument("--no-side-configs", action="store_true",
                     help="default run: skip the configs 1 and 3 legs that follow the headline workload")
     ap.add_argument("--calibrate-copy", action="store_true",
