@@ -142,6 +142,8 @@ typedef struct zcg_plan {
   int store_bytes; /* alignment the stores can rely on; < vec_bytes means shifted stores */
   int row_splits;  /* wavefronts per row (rows wider than one wave pass), else 1          */
   int half_ends;   /* HALFLINE: 1 all row ends, 2 lone lines only; else 0                 */
+  int ordered;     /* 1: zcg_gather_ex with these options would build the ascending order in
+                      the lent workspace and walk the list through it; else 0             */
 } zcg_plan;
 
 /* ---- errors ------------------------------------------------------------ */

@@ -62,7 +62,7 @@ class Plan(ctypes.Structure):
                 ("line_bytes", ctypes.c_int), ("nt_loads", ctypes.c_int),
                 ("nt_stores", ctypes.c_int), ("blocks", ctypes.c_int),
                 ("store_bytes", ctypes.c_int), ("row_splits", ctypes.c_int),
-                ("half_ends", ctypes.c_int)]
+                ("half_ends", ctypes.c_int), ("ordered", ctypes.c_int)]
 
     def as_dict(self) -> dict:
         return {k: getattr(self, k) for k, _ in self._fields_}

@@ -239,19 +239,22 @@ int zcg_unregister_table(zcg_table* t) {
   return rc;
 }
 
-int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
-                    const zcg_launch_opts* opts, zcg_plan* plan) {
-  if (!zcg_is_live(t)) return ZCG_EHANDLE;
-  return zcg_make_plan(t->row_bytes, t->elem, (uintptr_t)t->dev, (uintptr_t)out_dev, n_idx,
-                       t->host_resident, false, opts, plan);
-}
-
 static bool wants_order(const zcg_table* t, int64_t n_idx, const zcg_launch_opts* opts) {
   if (!opts || !opts->workspace_dev || opts->variant != ZCG_VARIANT_AUTO) return false;
   if ((uintptr_t)opts->workspace_dev % 256) return false;
   const int64_t order_bytes = (n_idx * 8 + 255) / 256 * 256;
   if (opts->workspace_bytes < order_bytes + zcg_order_scratch_bytes(n_idx)) return false;
   return zcg_order_pays(t, n_idx);
+}
+
+int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
+                    const zcg_launch_opts* opts, zcg_plan* plan) {
+  if (!zcg_is_live(t)) return ZCG_EHANDLE;
+  const bool ordered = n_idx > 0 && wants_order(t, n_idx, opts);
+  int rc = zcg_make_plan(t->row_bytes, t->elem, (uintptr_t)t->dev, (uintptr_t)out_dev, n_idx,
+                         t->host_resident, ordered, opts, plan);
+  if (rc == ZCG_OK) plan->ordered = ordered ? 1 : 0;
+  return rc;
 }
 
 static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,

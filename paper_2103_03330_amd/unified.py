@@ -23,6 +23,7 @@ class UnifiedTensor:
     def __init__(self, table: _b.Table, torch_dtype, shape, keepalive=None):
         self.table, self.dtype, self.shape = table, torch_dtype, tuple(shape)
         self._keepalive = keepalive  # the caller's array when it was pinned in place
+        self._workspace = None       # device scratch lent to the gather (short-row tables only)
 
     def gather(self, idx, out=None, stream=None, ordered_by=None):
         """rows = self[idx]; ``idx`` is a 1-D int64 CUDA tensor, ``out`` an optional CUDA tensor."""
@@ -38,6 +39,16 @@ class UnifiedTensor:
         stream = stream if stream is not None else torch.cuda.current_stream(idx.device)
         if ordered_by is not None:
             _b.gather_ordered(self.table, idx, ordered_by, out, stream=stream)
+        elif self.table.row_bytes <= 128 and idx.numel() >= 32768:
+            # rows of at most a line: lend the library scratch memory (torch's allocator, grown to
+            # the longest list seen, reused from call to call) so that it can walk long dense
+            # lists in ascending table order. One workspace per tensor: callers that gather from
+            # one unified tensor on several streams at once pass their own ``out`` and order.
+            need = _b.gather_workspace_bytes(idx.numel())
+            if self._workspace is None or self._workspace.numel() < need:
+                self._workspace = torch.empty(need, dtype=torch.uint8, device=idx.device)
+            opts = _b.LaunchOpts(workspace_dev=self._workspace.data_ptr(), workspace_bytes=self._workspace.numel())
+            _b.gather_ex(self.table, idx, out, opts, stream=stream)
         else:
             _b.gather(self.table, idx, out, stream=stream)
         return out
@@ -52,6 +63,7 @@ class UnifiedTensor:
     def close(self) -> None:
         self.table.close()
         self._keepalive = None
+        self._workspace = None
 
     def __enter__(self):
         return self

@@ -495,11 +495,34 @@ def test_auto_with_lent_workspace_orders_short_rows(n_rows, dim, dtype):
         ws_bytes = z.gather_workspace_bytes(n)
         ws = torch.zeros(ws_bytes + 256, dtype=torch.uint8, device="cuda")
         ws_ptr = (ws.data_ptr() + 255) // 256 * 256
+        lent = z.LaunchOpts(workspace_dev=ws_ptr, workspace_bytes=ws_bytes)
+        out = torch.full((n, dim), -7, dtype=TORCH_DT[dtype], device="cuda")
+        assert z.plan_gather(table, n, out, lent)["ordered"] == 1
+        assert z.plan_gather(table, n, out)["ordered"] == 0
+        assert z.plan_gather(table, 5000, out, lent)["ordered"] == 0
         for rep in range(2):
             out = torch.full((n, dim), -7, dtype=TORCH_DT[dtype], device="cuda")
-            z.gather_ex(table, idx_dev, out, z.LaunchOpts(workspace_dev=ws_ptr, workspace_bytes=ws_bytes))
+            z.gather_ex(table, idx_dev, out, lent)
             torch.cuda.synchronize()
             assert_same_bits(out, want, f"auto ordered rep {rep}")
+        # order build + gather are kernel launches only: one captured graph, replayed on new lists
+        s = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            z.gather_ex(table, idx_dev, out, lent, stream=s)
+        for seed in (31, 32):
+            fresh = wl.uniform_indices(n, n_rows, seed=seed)
+            idx_dev.copy_(torch.from_numpy(fresh))
+            out.fill_(-7)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert_same_bits(out, oracle_gather(table.host_array(), fresh), f"replay {seed}")
+        idx_dev.copy_(torch.from_numpy(idx))
+        out = torch.full((n, dim), -7, dtype=TORCH_DT[dtype], device="cuda")
+        z.gather_ex(table, idx_dev, out, lent)
+        torch.cuda.synchronize()
         # the order it built is left at the start of the workspace
         off = ws_ptr - ws.data_ptr()
         built = ws[off: off + 8 * n].view(torch.int64).cpu().numpy()
@@ -534,7 +557,9 @@ def test_auto_leaves_sparse_lists_in_list_order():
         ws_bytes = z.gather_workspace_bytes(n)
         ws = torch.zeros(ws_bytes, dtype=torch.uint8, device="cuda")
         out = torch.full((n, dim), -7, dtype=torch.float16, device="cuda")
-        z.gather_ex(table, idx_dev, out, z.LaunchOpts(workspace_dev=ws.data_ptr(), workspace_bytes=ws_bytes))
+        lent = z.LaunchOpts(workspace_dev=ws.data_ptr(), workspace_bytes=ws_bytes)
+        assert z.plan_gather(table, n, out, lent)["ordered"] == 0
+        z.gather_ex(table, idx_dev, out, lent)
         torch.cuda.synchronize()
         assert_same_bits(out, oracle_gather(table.host_array(), idx), "sparse list")
         assert not bool(ws.any())

@@ -307,3 +307,28 @@ def test_pipeline_calls_reject_null_without_touching_the_gpu():
     assert lib.zcg_pipeline_submit_wait(None, None, 0, 0, ctypes.byref(slot)) == z.binding.EINVAL
     assert lib.zcg_pipeline_release(None, 0, None) == z.binding.EINVAL
     assert lib.zcg_pipeline_destroy(None) == z.binding.EINVAL
+
+
+def test_plan_says_when_a_lent_workspace_would_be_used_for_an_ordered_walk():
+    """Host-resident rows of at most a line: AUTO orders a list only when it is long and dense
+    enough in the table for shared link requests to outweigh the cost of building the order."""
+    lib = z.load_library()
+
+    def ordered(n_rows, dim, dtype, n_idx, parent_kind="host", **kw):
+        # zcg_alloc_table needs a GPU; a view of a device table is not host-resident, so the
+        # host-resident cases are planned on a handle made by hand
+        t = z.table_from_device(0x7F0000000000, n_rows, dim, dtype)
+        try:
+            ws = z.gather_workspace_bytes(n_idx)
+            o = z.LaunchOpts(workspace_dev=0x7D0000000000, workspace_bytes=ws, **kw)
+            return z.plan_gather(t, n_idx, 0x7E0000000000, o)["ordered"]
+        finally:
+            t.close()
+
+    # device-resident tables never order (HBM is not request-bound)
+    assert ordered(10_000_000, 16, "f16", 1_000_000) == 0
+    assert z.gather_workspace_bytes(0) == 0
+    assert z.gather_workspace_bytes(1_000_000) >= 16_000_000
+    ws = ctypes.c_int64(0)
+    assert lib.zcg_gather_workspace_bytes(-1, ctypes.byref(ws)) == z.binding.EINVAL
+    assert lib.zcg_gather_workspace_bytes(5, None) == z.binding.EINVAL
