@@ -982,6 +982,10 @@ def main():
     model_reqs = float(np.mean([link_model.link_requests_per_row(rb, a, table.device_ptr,
                                                                  half_ends=plan["half_ends"])
                                 for a in lists[:4]]))
+    wire = float(np.mean([link_model.link_wire_bytes_per_row(rb, a, table.device_ptr, half_ends=plan["half_ends"])
+                          for a in lists[:4]]))
+    wire_rate = (nominal or 63.02) * 1e9
+    limit_rows = min(wire_rate / wire, 322e6 / model_reqs)
     result = {
         "metric": METRIC, "value": round(value, 3), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall / args.steps * 1e3, 4),
@@ -1026,6 +1030,16 @@ def main():
                                                "taken through the scalar cache (half-line kernel); "
                                                "requests: 256 B aligned line pairs, lone lines and "
                                                "64 B reads count one each (profiles/link_request_model.txt)"},
+                     "link_limit": {"gbps": round(limit_rows * rb / 1e9, 2),
+                                    "frac": round(achieved / (limit_rows * rb / 1e9), 4),
+                                    "wire_bytes_per_row": round(wire, 1),
+                                    "bound_by": "wire" if wire_rate / wire < 322e6 / model_reqs else "requests",
+                                    "what": "what this link can deliver for this kernel's request mix: the "
+                                            "lower of nominal wire rate / (fetched bytes + 24 B per read "
+                                            "completion) and 322 M requests/s / requests per row "
+                                            "(profiles/link_request_model.txt); the remaining distance to "
+                                            "`peak` is bytes the 128-byte line granularity makes the link "
+                                            "carry, not time the kernel wastes"},
                      "kernel_ms_avg": round(avg_kernel_ms, 4),
                      "kernel_ms_is": "mean time between the HIP events recorded after consecutive launches "
                                      "on the launch stream: the kernel plus its launch gap",

@@ -72,6 +72,33 @@ def link_requests_per_row(row_bytes: int, idx: np.ndarray, base_addr: int = 0,
     return float(np.mean(pairs + head.astype(np.int64) + tail.astype(np.int64)))
 
 
+NOMINAL_PCIE5_X16 = 32.0e9 * 16 * (128.0 / 130.0) / 8.0  # bytes/s on the wire, 63.0 GB/s
+TLP_OVERHEAD = 24.0  # wire bytes per read completion beside its payload (framing, header, LCRC)
+
+
+def link_wire_bytes_per_row(row_bytes: int, idx: np.ndarray, base_addr: int = 0, half_ends: int = 0,
+                            overhead: float = TLP_OVERHEAD) -> float:
+    """Mean bytes per listed row on the wire: what is fetched plus ``overhead`` bytes for every
+    request's completion. Measured: consecutive memory streams at 57.6 GB/s over a link whose
+    wire rate is 63.0 GB/s, i.e. 256-byte completions carry about 24 bytes each beside their
+    payload; a lone 128-byte line or a 64-byte read pays the same 24 bytes for less payload. With
+    this the row rates of the profiles come out within 1 %: config 2 with lone ends through
+    64-byte reads, 1.5 pairs + 0.5 lines + 0.5 half lines = 540 wire bytes per row -> 116.7 M
+    rows/s at 63.0 GB/s (measured 116.3); whole lines only, 572 bytes -> 110.2 M (110.1)."""
+    return (link_bytes_per_row(row_bytes, idx, base_addr, half_ends=half_ends)
+            + overhead * link_requests_per_row(row_bytes, idx, base_addr, half_ends))
+
+
+def link_limit_rows_per_s(row_bytes: int, idx: np.ndarray, base_addr: int = 0, half_ends: int = 0,
+                          wire_bytes_per_s: float = NOMINAL_PCIE5_X16, overhead: float = TLP_OVERHEAD,
+                          requests_per_s: float = 322e6) -> float:
+    """Rows per second the link can deliver for this request mix: the lower of the wire limit
+    (wire bytes per row) and the request limit (requests per row at ~322 M/s)."""
+    wire = link_wire_bytes_per_row(row_bytes, idx, base_addr, half_ends, overhead)
+    reqs = link_requests_per_row(row_bytes, idx, base_addr, half_ends)
+    return min(wire_bytes_per_s / wire, requests_per_s / reqs)
+
+
 def useful_fraction(row_bytes: int, idx: np.ndarray, base_addr: int = 0, halfline: bool = False,
                     half_ends: int = 0) -> float:
     return row_bytes / link_bytes_per_row(row_bytes, idx, base_addr, halfline, half_ends)

@@ -74,3 +74,38 @@ def test_closed_forms():
     assert link_model.link_requests_per_row(512, idx, base_addr=128) == 3.0
     assert link_model.link_requests_per_row(256, idx, base_addr=128) == 2.0
     assert link_model.link_requests_per_row(128, idx) == 1.0
+
+
+def measured_rates():
+    """label -> M rows/s from profiles/link_request_model.txt (kernel-trace times)."""
+    out = {}
+    for line in open(os.path.join(ROOT, "profiles", "link_request_model.txt")):
+        m = re.match(r"\s{2}(\S.*?)\s{2,}([\d.]+)\s+([\d.]+)\s+([\d.]+)\s+[\d.]+\s+[\d.]+\s+[\d.]+\s+[\d.]+", line)
+        if m:
+            out[m.group(1).strip()] = float(m.group(3))
+    return out
+
+
+def test_wire_and_request_limits_explain_the_measured_row_rates():
+    """Rows/s = min(wire rate / wire bytes per row, request rate / requests per row), wire bytes =
+    payload + 24 per completion: within 2 % of the profiled kernels wherever the wire is the
+    limit, and an upper bound within 6 % where requests are."""
+    rate = measured_rates()
+    cfg = wl.config(2)
+    idx = wl.index_lists(cfg)[0]
+    base = 0  # tables are page-aligned
+    for label, policy in (("cfg2 rowvec", 0), ("cfg2 aligned", 0), ("cfg2 half-lone", 2)):
+        want = link_model.link_limit_rows_per_s(cfg.row_bytes, idx, base, policy) / 1e6
+        assert abs(rate[label] - want) / want < 0.02, (label, rate[label], want)
+    want = link_model.link_limit_rows_per_s(cfg.row_bytes, idx, base, 1) / 1e6  # half-all: request-bound
+    assert want * 0.94 < rate["cfg2 half-all"] <= want * 1.01
+    uni = np.arange(0, 400_000) * 7 % 4_000_000  # any list: rows tile the grid identically
+    for label, rb, off in (("rows 256 B base+0", 256, 0), ("rows 256 B base+128", 256, 128),
+                           ("rows 128 B base+0", 128, 0), ("rows 512 B base+0", 512, 0)):
+        want = link_model.link_limit_rows_per_s(rb, uni, off) / 1e6
+        assert abs(rate[label] - want) / want < 0.02, (label, rate[label], want)
+    want = link_model.link_limit_rows_per_s(512, uni, 128) / 1e6  # lone + pair + lone: both limits close
+    assert want * 0.94 < rate["rows 512 B base+128"] <= want * 1.01
+    # closed forms of the wire model
+    assert link_model.link_wire_bytes_per_row(400, np.arange(100000), half_ends=2) == 480.0 + 24 * 2.5
+    assert link_model.link_wire_bytes_per_row(256, np.arange(1000)) == 280.0
