@@ -111,7 +111,7 @@ typedef struct zcg_launch_opts {
                       64-byte scalar read; 2 = only ends whose line would otherwise be
                       requested alone (its partner in the 256-byte aligned pair is not
                       part of the row), which never adds a link request. Default: 1 for
-                      rows of 1 KiB and more, 2 for shorter rows.                       */
+                      rows of 768 bytes and more, 2 for shorter rows.                   */
   void* workspace_dev;     /* optional: device memory, CALLER-OWNED, 256-byte aligned, that
                       the call may overwrite while it runs on its stream (free to reuse
                       once the stream has passed the call; two calls that overlap in

@@ -89,11 +89,12 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     variant = (row_bytes < line || (whole_lines && !off_pair_grid)) ? ZCG_VARIANT_ROWVEC
                                                                     : ZCG_VARIANT_ALIGNED;
     // Unaligned rows of more than a line over the host link: row ends that fit half a line go
-    // through 64-byte scalar reads. From 1 KiB on every such end does (measured +2...4 % on
-    // 1,032...2,408-byte rows with 8- or 16-byte lanes: one more request per 8+ lines, 64 bytes
-    // less); on shorter rows only ends whose line would be requested alone anyway, which saves
-    // bytes without adding requests (measured +1.5...4 % on 160...800-byte rows, +6 % on
-    // sampled minibatches of 400-byte rows; converting every end there loses 6 %).
+    // through 64-byte scalar reads. From 768 bytes on every such end does (measured +1.3...4 % on
+    // 816...2,408-byte rows with 8- or 16-byte lanes: one more request per 6+ lines, 40 wire
+    // bytes less; break-even at 720 bytes); on shorter rows only ends whose line would be
+    // requested alone anyway, which saves bytes without adding requests (measured +1.5...4 % on
+    // 160...720-byte rows, +6 % on sampled minibatches of 400-byte rows; converting every end
+    // there loses 1...8 %, as such rows are close to the link's request limit).
     // Rows that tile half lines exactly (16, 32 or 64 bytes on a 64-byte aligned base) over the
     // host link: each is one 64-byte scalar read instead of one lone 128-byte line, the same
     // request count and half the bytes (measured +1...3 % from 110 k rows per call on, -0.5 % at
@@ -119,7 +120,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
 
   plan->variant = variant;
   plan->half_ends = variant != ZCG_VARIANT_HALFLINE ? 0
-                    : (o.half_ends ? o.half_ends : (row_bytes >= 1024 ? 1 : 2));
+                    : (o.half_ends ? o.half_ends : (row_bytes >= 768 ? 1 : 2));
   plan->row_splits = 1;
   plan->line_bytes = line;
   plan->unroll = unroll;

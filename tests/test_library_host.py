@@ -211,7 +211,9 @@ def test_plan_splits_long_rows_of_short_lists():
 def test_plan_half_line_policy():
     assert plan(100, "f32")["half_ends"] == 0  # not a half-line kernel
     assert plan(100, "f32", variant=z.VARIANT_HALFLINE)["half_ends"] == 2  # short rows: lone ends only
-    assert plan(602, "f32", variant=z.VARIANT_HALFLINE)["half_ends"] == 1  # 1 KiB and more: every end
+    assert plan(602, "f32", variant=z.VARIANT_HALFLINE)["half_ends"] == 1  # 768 bytes and more: every end
+    assert plan(193, "f32", variant=z.VARIANT_HALFLINE)["half_ends"] == 1
+    assert plan(191, "f32", variant=z.VARIANT_HALFLINE)["half_ends"] == 2
     assert plan(100, "f32", variant=z.VARIANT_HALFLINE, half_ends=1)["half_ends"] == 1
     assert plan(602, "f32", variant=z.VARIANT_HALFLINE, half_ends=2)["half_ends"] == 2
 
