@@ -301,6 +301,18 @@ int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
                     const zcg_launch_opts* opts, zcg_plan* plan);
 
 /*
+ * The same planning for a table described by numbers instead of a handle: rows of row_bytes
+ * bytes made of elem_bytes-byte elements (1, 2, 4 or 8) starting at table_addr, output at
+ * out_addr, host_resident != 0 for a table read over the host link. Host-only, no GPU needed:
+ * lets a caller (or a test) see which kernel and launch shape any address, row size and option
+ * set would get. `ordered` in the result tells whether a lent workspace would be used, judged
+ * with n_rows rows in the table. Errors as zcg_gather_ex's argument checks.
+ */
+int zcg_plan_shape(int64_t row_bytes, int elem_bytes, uint64_t table_addr, uint64_t out_addr,
+                   int64_t n_rows, int64_t n_idx, int host_resident, const zcg_launch_opts* opts,
+                   zcg_plan* plan);
+
+/*
  * Debug helper, SYNCHRONOUS: counts entries of idx_dev outside [0, n_rows) on
  * the GPU, waits, and writes the count to *n_bad_host (host). Allocates and
  * frees 8 bytes of device memory.

@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     alloc_table, device_cu_count, stream_create_cu_mask, stream_destroy, table_view,
     cpu_gather_memcpy, cpu_gather_memcpy_chunked, gather, gather_ex, gather_ordered, gather_variant,
     make_order, make_order_static, order_workspace_bytes, gather_workspace_bytes, STATIC_ORDER_MAX_IDX,
-    last_hip_error, load_library, pipeline_create, pinned_alloc, pinned_free, plan_gather,
+    last_hip_error, load_library, pipeline_create, pinned_alloc, pinned_free, plan_gather, plan_shape,
     register_table, strerror, table_from_device, unregister_table, validate_indices, version,
 )
 from .unified import UnifiedTensor, to_unified  # noqa: F401,E402

@@ -41,7 +41,7 @@ EXPORTS = [
     "zcg_pipeline_finish", "zcg_pipeline_next", "zcg_pipeline_acquire",
     "zcg_pipeline_release", "zcg_pipeline_destroy", "zcg_gather_ordered",
     "zcg_order_workspace_bytes", "zcg_make_order", "zcg_table_view", "zcg_gather_workspace_bytes",
-    "zcg_make_order_static",
+    "zcg_make_order_static", "zcg_plan_shape",
 ]
 
 
@@ -126,6 +126,8 @@ def load_library() -> ctypes.CDLL:
         "zcg_order_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
         "zcg_make_order": (i32, [vp, i64, i64, vp, vp, i64, vp]),
         "zcg_make_order_static": (i32, [vp, i64, i64, vp, vp]),
+        "zcg_plan_shape": (i32, [i64, i32, ctypes.c_uint64, ctypes.c_uint64, i64, i64, i32,
+                                 ctypes.POINTER(LaunchOpts), ctypes.POINTER(Plan)]),
         "zcg_table_view": (i32, [vp, i64, i64, i64, i32, pvp]),
         "zcg_gather_workspace_bytes": (i32, [i64, ctypes.POINTER(i64)]),
     }
@@ -303,6 +305,17 @@ def plan_gather(table: Table, n_idx: int, out_dev, opts: Optional[LaunchOpts] = 
                                         ctypes.byref(opts) if opts is not None else None,
                                         ctypes.byref(plan))
     _check(rc, "zcg_plan_gather")
+    return plan.as_dict()
+
+
+def plan_shape(row_bytes: int, elem_bytes: int, table_addr: int, out_addr: int, n_rows: int, n_idx: int,
+               host_resident: bool, opts: Optional[LaunchOpts] = None) -> dict:
+    """zcg_plan_shape: the launch plan for a table given by numbers (host-only)."""
+    plan = Plan()
+    rc = load_library().zcg_plan_shape(row_bytes, elem_bytes, table_addr, out_addr, n_rows, n_idx,
+                                       1 if host_resident else 0,
+                                       ctypes.byref(opts) if opts is not None else None, ctypes.byref(plan))
+    _check(rc, "zcg_plan_shape")
     return plan.as_dict()
 
 

@@ -257,6 +257,23 @@ int zcg_plan_gather(const zcg_table* t, int64_t n_idx, const void* out_dev,
   return rc;
 }
 
+int zcg_plan_shape(int64_t row_bytes, int elem_bytes, uint64_t table_addr, uint64_t out_addr,
+                   int64_t n_rows, int64_t n_idx, int host_resident, const zcg_launch_opts* opts,
+                   zcg_plan* plan) {
+  if (!plan || n_rows < 1 || row_bytes < 1) return ZCG_EINVAL;
+  zcg_table t = {};  // never registered: only the fields the planning reads
+  t.kind = host_resident ? ZCG_KIND_ALLOCATED : ZCG_KIND_DEVICE;
+  t.host_resident = host_resident != 0;
+  t.elem = elem_bytes;
+  t.n_rows = n_rows;
+  t.row_bytes = row_bytes;
+  const bool ordered = n_idx > 0 && wants_order(&t, n_idx, opts);
+  int rc = zcg_make_plan(row_bytes, elem_bytes, (uintptr_t)table_addr, (uintptr_t)out_addr, n_idx,
+                         t.host_resident, ordered, opts, plan);
+  if (rc == ZCG_OK) plan->ordered = ordered ? 1 : 0;
+  return rc;
+}
+
 static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64_t* order_dev,
                          int64_t n_idx, void* out_dev, void* stream, const zcg_launch_opts* opts) {
   if (!zcg_is_live(t)) return ZCG_EHANDLE;
