@@ -41,6 +41,7 @@ extern "C" {
 #define ZCG_EBUSY (-9)   /* pipeline: the next buffer has not been released yet */
 #define ZCG_ETIMEDOUT (-10) /* pipeline: a bounded wait ran out                   */
 #define ZCG_ECLOSED (-11)   /* pipeline: the producer has finished                */
+#define ZCG_ECAPACITY (-12) /* input larger than a fixed capacity of the entry point */
 
 /* ---- element types: only the size matters, payload bits are never read -- */
 #define ZCG_F16 1 /* 2-byte elements (fp16, bf16, int16)         */
@@ -276,8 +277,9 @@ int zcg_make_order(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_
  * Same order, same kernels; the temporary memory is a static device array inside
  * the library (8.5 MiB on every GPU the library runs on, held until the process
  * ends) instead of a workspace argument. The call allocates nothing.
- *   n_idx <= ZCG_STATIC_ORDER_MAX_IDX (ZCG_EINVAL beyond); other arguments and
- *   errors as zcg_make_order. Works on the current device.
+ *   n_idx <= ZCG_STATIC_ORDER_MAX_IDX (ZCG_ECAPACITY beyond: use zcg_make_order with
+ *   a workspace); other arguments and errors as zcg_make_order. Works on the
+ *   current device.
  * Every call on one GPU shares that GPU's array: two calls that overlap in time
  * on one GPU (different streams, no ordering between them) race and give a wrong
  * order; calls on one stream, or ordered by events, are fine. Nothing in the array

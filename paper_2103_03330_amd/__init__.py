@@ -7,7 +7,7 @@ The work is done by hand-written gfx950 kernels behind a C ABI
 (``include/zcgather.h``); this package is the thin Python binding.
 """
 from .binding import (  # noqa: F401
-    EBUSY, ECLOSED, ETIMEDOUT,
+    EBUSY, ECAPACITY, ECLOSED, ETIMEDOUT,
     ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER, ALLOC_UNCACHED, B8, B64, F16, F32, VARIANT_ALIGNED, VARIANT_AUTO, VARIANT_HALFLINE,
     VARIANT_NAIVE, VARIANT_NAMES, VARIANT_ROWVEC, LaunchOpts, MaskedStream, Pipeline, Table, ZcgError,
     alloc_table, device_cu_count, stream_create_cu_mask, stream_destroy, table_view,

@@ -19,8 +19,8 @@ import numpy as np
 from . import build as _build
 
 # status codes / constants (include/zcgather.h)
-OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE, EBUSY, ETIMEDOUT, ECLOSED = (
-    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11)
+OK, EINVAL, EDTYPE, EHANDLE, EHIP, ENOMEM, EALIGN, EALIAS, ERANGE, EBUSY, ETIMEDOUT, ECLOSED, ECAPACITY = (
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10, -11, -12)
 F16, F32, B8, B64 = 1, 2, 3, 4
 ALLOC_DEFAULT, ALLOC_NONCOHERENT, ALLOC_NUMA_USER, ALLOC_UNCACHED = 0, 1, 2, 4
 VARIANT_AUTO, VARIANT_NAIVE, VARIANT_ROWVEC, VARIANT_ALIGNED, VARIANT_HALFLINE = 0, 1, 2, 3, 4

@@ -119,6 +119,7 @@ const char* zcg_strerror(int status) {
     case ZCG_EBUSY: return "buffer not released by the consumer";
     case ZCG_ETIMEDOUT: return "wait timed out";
     case ZCG_ECLOSED: return "pipeline finished by the producer";
+    case ZCG_ECAPACITY: return "input larger than the entry point's fixed capacity";
     default: return "unknown status";
   }
 }

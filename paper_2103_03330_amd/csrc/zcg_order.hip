@@ -334,11 +334,11 @@ extern "C" {
 
 int zcg_make_order_static(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_t* order_dev,
                           void* stream) {
-  if (n_idx < 0 || n_rows < 1 || n_idx > kStaticMaxIdx) return ZCG_EINVAL;
+  if (n_idx < 0 || n_rows < 1) return ZCG_EINVAL;
+  if (n_idx > kStaticMaxIdx || zcg_order_scratch_bytes(n_idx) > kStaticScratchBytes) return ZCG_ECAPACITY;
   if (n_idx == 0) return ZCG_OK;
   if (!idx_dev || !order_dev) return ZCG_EINVAL;
   if (((uintptr_t)idx_dev | (uintptr_t)order_dev) % 8) return ZCG_EALIGN;
-  if (zcg_order_scratch_bytes(n_idx) > kStaticScratchBytes) return ZCG_EINVAL;
   void* scratch = nullptr;
   hipError_t e = static_scratch(&scratch);
   if (e != hipSuccess) return zcg_fail_hip(e);

@@ -53,7 +53,7 @@ def test_probe_header_and_library_agree_on_exports():
 
 
 def test_status_strings():
-    for code in range(0, -12, -1):
+    for code in range(0, -13, -1):
         assert z.strerror(code) != "unknown status"
     assert z.strerror(-99) == "unknown status"
 
@@ -334,3 +334,12 @@ def test_plan_says_when_a_lent_workspace_would_be_used_for_an_ordered_walk():
     ws = ctypes.c_int64(0)
     assert lib.zcg_gather_workspace_bytes(-1, ctypes.byref(ws)) == z.binding.EINVAL
     assert lib.zcg_gather_workspace_bytes(5, None) == z.binding.EINVAL
+
+
+def test_static_order_builder_refuses_oversized_lists_before_touching_the_gpu():
+    lib = z.load_library()
+    assert lib.zcg_make_order_static(0x1000, z.STATIC_ORDER_MAX_IDX + 1, 100, 0x2000, None) == z.binding.ECAPACITY
+    assert lib.zcg_make_order_static(0x1000, -1, 100, 0x2000, None) == z.binding.EINVAL
+    assert lib.zcg_make_order_static(0x1000, 8, 0, 0x2000, None) == z.binding.EINVAL
+    assert lib.zcg_make_order_static(None, 0, 100, None, None) == 0
+    assert lib.zcg_make_order_static(0x1004, 8, 100, 0x2000, None) == z.binding.EALIGN

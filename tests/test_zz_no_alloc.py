@@ -46,7 +46,8 @@ def test_static_scratch_order_matches_workspace_order():
     # sizes beyond the array, and the usual argument errors, are refused before any launch
     idx_dev = torch.zeros(8, dtype=torch.int64, device="cuda")
     order = torch.zeros(8, dtype=torch.int64, device="cuda")
-    assert lib.zcg_make_order_static(idx_dev.data_ptr(), z.STATIC_ORDER_MAX_IDX + 1, 100, order.data_ptr(), None) == -1
+    assert lib.zcg_make_order_static(idx_dev.data_ptr(), z.STATIC_ORDER_MAX_IDX + 1, 100, order.data_ptr(), None) == -12
+    assert "capacity" in z.strerror(-12)
     assert lib.zcg_make_order_static(idx_dev.data_ptr(), -1, 100, order.data_ptr(), None) == -1
     assert lib.zcg_make_order_static(idx_dev.data_ptr(), 8, 0, order.data_ptr(), None) == -1
     assert lib.zcg_make_order_static(None, 8, 100, order.data_ptr(), None) == -1
