@@ -120,7 +120,7 @@ typedef struct zcg_launch_opts {
                       zcg_gather_workspace_bytes(n_idx) bytes, zcg_gather_ex walks lists
                       of host-resident rows of at most 128 bytes in ascending table
                       order where that pays: it builds the order in the workspace with
-                      a few kernels of its own on the same stream (about 0.1 ms), then
+                      a few kernels of its own on the same stream (0.04-0.09 ms), then
                       gathers through it. The result is the same bit for bit; listed
                       rows that share a line or a 256-byte pair of lines then share a
                       link request, so the walk pays for long lists that are dense in
@@ -260,7 +260,7 @@ int zcg_gather_ordered(const zcg_table* t, const int64_t* idx_dev, const int64_t
  * count, a prefix and a scatter kernel; deterministic). Equal indices keep their
  * list order. Asynchronous on `stream`; allocates nothing: all temporary memory is
  * the caller's workspace (device, 256-byte aligned, at least
- * zcg_order_workspace_bytes(n_idx) bytes = about 8 bytes per entry plus 0.3 MB,
+ * zcg_order_workspace_bytes(n_idx) bytes = about 9 bytes per entry,
  * free to reuse once the stream has passed the call). order_dev itself is used as
  * a second buffer while the order is built. n_rows bounds the index values: only
  * the bits below it are sorted, so entries outside [0, n_rows) still yield a
@@ -275,7 +275,7 @@ int zcg_make_order(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_
  * zcg_make_order for callers that cannot allocate or lend device memory: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same order, same kernels; the temporary memory is a static device array inside
- * the library (8.5 MiB on every GPU the library runs on, held until the process
+ * the library (9.1 MiB on every GPU the library runs on, held until the process
  * ends) instead of a workspace argument. The call allocates nothing.
  *   n_idx <= ZCG_STATIC_ORDER_MAX_IDX (ZCG_ECAPACITY beyond: use zcg_make_order with
  *   a workspace); other arguments and errors as zcg_make_order. Works on the

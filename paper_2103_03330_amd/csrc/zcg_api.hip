@@ -83,12 +83,13 @@ int zcg_fail_hip(hipError_t e) {
 // requests per microsecond); walked in ascending table order, listed rows that share a line or
 // a 256-byte pair of lines share a request. With lambda listed rows per pair on average, a
 // fraction 1 - (1 - exp(-lambda)) / lambda of the requests goes away; measured, about 0.6 of
-// that is realised (1 M entries over 10 M rows: 32-byte rows 11.1 -> 14.5 GB/s, 64-byte rows
-// 21.5 -> 25.0, 128-byte rows 41.1 -> 46.0). Building the order is launch-bound: about 20 us
-// plus 25 us per 8-bit digit of the row number. A caller that lends workspace gets the ordered
-// walk from AUTO whenever the saving clearly exceeds that cost -- long lists that are dense in
-// their table -- and the plain walk otherwise (262,144 entries over 10 M rows: ordering would
-// save 4 % and cost 10 %).
+// that is realised (1 M entries over 10 M rows: 32-byte rows 10.9 -> 14.2 GB/s, 64-byte rows
+// 21.5 -> 24.4, 128-byte rows 40.7 -> 45.5). Building the order costs about 12 us per 8-bit
+// digit of the row number plus 16 ns per 1,000 entries and digit (37 us for 24-bit row numbers
+// and short lists, 84 us for 1 M entries). A caller that lends workspace gets the ordered walk
+// from AUTO whenever the saving clearly exceeds that cost -- long lists that are dense in their
+// table -- and the plain walk otherwise (262,144 entries over 10 M rows: ordering would save
+// 4 % and cost 6 %).
 bool zcg_order_pays(const zcg_table* t, int64_t n_idx) {
   if (!t->host_resident || t->row_bytes > 128 || n_idx < 32768 || n_idx > (int64_t)UINT32_MAX)
     return false;
@@ -97,7 +98,7 @@ bool zcg_order_pays(const zcg_table* t, int64_t n_idx) {
   const double saved_us = 0.6 * shared * (double)n_idx / 320.0;
   int bits = 1;
   while (bits < 63 && ((int64_t)1 << bits) < t->n_rows) ++bits;
-  const double build_us = 20.0 + 25.0 * (double)((bits + 7) / 8);
+  const double build_us = (double)((bits + 7) / 8) * (12.0 + 0.016e-3 * (double)n_idx);
   return saved_us > 1.25 * build_us;
 }
 

@@ -30,7 +30,7 @@
 // the process ends. In host code this name is only a handle for hipGetSymbolAddress, never an
 // address to pass on.
 constexpr int64_t kStaticMaxIdx = ZCG_STATIC_ORDER_MAX_IDX;
-constexpr int64_t kStaticScratchBytes = kStaticMaxIdx * 8 + (512 << 10);
+constexpr int64_t kStaticScratchBytes = kStaticMaxIdx * 8 + (1 << 20) + (64 << 10);  // buffer + counts + bin sizes
 static __device__ __align__(256) unsigned char zcg_order_static_scratch[kStaticScratchBytes];
 
 namespace {
@@ -44,11 +44,12 @@ constexpr int64_t kMaxBlocks = 1024;  // cap on the grid: the per-bin prefix is 
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
-// Elements each wavefront owns: 1024, more for lists beyond 4 M entries so that the grid
-// stays within kMaxBlocks; always a multiple of the wave size.
+// Elements each wavefront owns: 256 (four steps of 64; short stretches mean many wavefronts in
+// flight, and a pass is bound by the latency of its dependent steps, not by bytes), more for
+// lists beyond 1 M entries so that the grid stays within kMaxBlocks; a multiple of the wave size.
 int64_t wave_span(int64_t n) {
   const int64_t need = (n + kMaxBlocks * kWavesPerBlock - 1) / (kMaxBlocks * kWavesPerBlock);
-  return need <= 1024 ? 1024 : round_up(need, kWave);
+  return need <= 256 ? 256 : round_up(need, kWave);
 }
 int64_t grid_blocks(int64_t n) {
   const int64_t per_block = wave_span(n) * kWavesPerBlock;
@@ -209,12 +210,16 @@ zcg_k_order_scatter(PassIO io, int64_t n, int64_t span, int shift, unsigned mask
   __syncthreads();
   // 3. every wavefront walks its stretch again in list order, 64 entries at a time; entries of
   //    one step with the same digit are ranked by lane, and only this wavefront touches next[w]
+  //    (the next step's entry is fetched while this step's is ranked and stored)
+  uint64_t key_next = 0;
+  uint32_t pos_next = 0;
+  if (begin + lane < end) fetch<SRC>(io, begin + lane, key_next, pos_next);
   for (int64_t i0 = begin; i0 < end; i0 += kWave) {
     const int64_t i = i0 + lane;
     const bool active = i < end;
-    uint64_t key = 0;
-    uint32_t pos = 0;
-    if (active) fetch<SRC>(io, i, key, pos);
+    const uint64_t key = key_next;
+    const uint32_t pos = pos_next;
+    if (i + kWave < end) fetch<SRC>(io, i + kWave, key_next, pos_next);
     const unsigned d = (unsigned)(key >> shift) & mask;
     const uint64_t peers = same_digit_lanes(d, active);
     const unsigned rank = (unsigned)__popcll(peers & (((uint64_t)1 << lane) - 1u));

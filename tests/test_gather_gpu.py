@@ -547,9 +547,9 @@ def test_auto_with_lent_workspace_orders_short_rows(n_rows, dim, dtype):
 
 
 def test_auto_leaves_sparse_lists_in_list_order():
-    """200 k entries over 6 M rows of 32 bytes: about a quarter of a listed row per 256-byte pair,
-    too few shared requests to pay for building the order; the workspace stays untouched."""
-    n_rows, dim, n = 6_000_000, 16, 200_003
+    """200 k entries over 12 M rows of 32 bytes: an eighth of a listed row per 256-byte pair, too
+    few shared requests to pay for building the order; the workspace stays untouched."""
+    n_rows, dim, n = 12_000_000, 16, 200_003
     table = host_table(n_rows, dim, "f16", seed=3)
     try:
         idx = wl.uniform_indices(n, n_rows, seed=29)
