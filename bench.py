@@ -91,11 +91,11 @@ def read_profile_traffic(name, plan):
         return None, f"profile incomplete: {name} lacks the per-row byte figures"
 
 
-def run_side_config(args, z, wl, np, torch, k, link_peak, n_cores):
+def run_side_config(args, z, wl, np, torch, k, link_peak, n_cores, n_lists=8):
     """One of the other single-GPU workloads, measured like the headline one (same step, same
     clocks) but outside its timed region: wall-clock GB/s over `steps` steps, the kernel alone
     from HIP events, and the DMA method on the same lists."""
-    cfg, table, lists, info = build_workload(z, wl, k, 8, z.ALLOC_DEFAULT, args.max_table_gb)
+    cfg, table, lists, info = build_workload(z, wl, k, n_lists, z.ALLOC_DEFAULT, args.max_table_gb)
     try:
         rb = cfg.row_bytes
         tdt = torch.float32 if cfg.dtype == "f32" else torch.float16
@@ -106,15 +106,15 @@ def run_side_config(args, z, wl, np, torch, k, link_peak, n_cores):
         plan = z.plan_gather(table, lists[0].size, outs[0])
         steps = max(5, min(args.steps, 100))
         for i in range(max(2, min(args.warmup, 10))):
-            z.gather(table, idx_dev[i % 8], outs[i & 1], n_idx=lists[i % 8].size, stream=stream)
+            z.gather(table, idx_dev[i % n_lists], outs[i & 1], n_idx=lists[i % n_lists].size, stream=stream)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]  # one per launch, as in main()
         torch.cuda.synchronize()
         t0, rows = time.perf_counter(), 0
         ev[0].record(stream)
         for i in range(steps):
-            z.gather(table, idx_dev[i % 8], outs[i & 1], n_idx=lists[i % 8].size, stream=stream)
+            z.gather(table, idx_dev[i % n_lists], outs[i & 1], n_idx=lists[i % n_lists].size, stream=stream)
             ev[i + 1].record(stream)
-            rows += lists[i % 8].size
+            rows += lists[i % n_lists].size
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         kern_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]))
@@ -129,12 +129,14 @@ def run_side_config(args, z, wl, np, torch, k, link_peak, n_cores):
             torch.cuda.synchronize()
             t0, r = time.perf_counter(), 0
             for i in range(max(3, min(steps, 16))):
-                fn(i % 8)
+                fn(i % n_lists)
                 torch.cuda.synchronize()
-                r += lists[i % 8].size
+                r += lists[i % n_lists].size
             best = max(best, r * rb / (time.perf_counter() - t0) / 1e9)
         z.pinned_free(staging)
-        return {"workload": f"{cfg.name}: {cfg.dtype} table {info['n_rows']} x {cfg.dim} ({rb} B rows)",
+        return {"workload": f"{cfg.name}: {cfg.dtype} table {info['n_rows']} x {cfg.dim} ({rb} B rows), "
+                            f"{n_lists} distinct minibatches cycled" + (f"; {info['note']}" if info["note"] else ""),
+                "setup_s": {"table_s": info["table_s"], "sampler_s": info["sampler_s"]},
                 "value": round(value, 3), "unit": "GB/s", "steps": steps,
                 "ms_per_step": round(wall / steps * 1e3, 4), "rows_per_step_avg": round(rows / steps, 1),
                 "fraction_of_link_peak": round(value / link_peak, 4),
@@ -173,6 +175,8 @@ def main():
                     help="config 5: run one point only, by name (e.g. cfg5_f16_d16; for kernel-trace profiles)")
     ap.add_argument("--no-side-configs", action="store_true",
                     help="default run: skip the configs 1 and 3 legs that follow the headline workload")
+    ap.add_argument("--no-config4", action="store_true",
+                    help="default run: skip the config 4 leg (needs 57 GB of pinned host memory)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 256 MiB device copy, as the known-size reference for counters")
     args = ap.parse_args()
@@ -480,9 +484,14 @@ def main():
                                   "cpu": _cpu_model()}
     table.close()
     if args.config == 2 and not args.no_baselines and not args.no_side_configs:
-        # the other workloads that set up in about a second (51 MB and 561 MB tables), same clocks
+        # the other single-GPU workloads, same clocks: configs 1 and 3 set up in under a second;
+        # config 4 (56.8 GB pinned table, about 6 s to allocate, fill and sample) runs the first
+        # min(steps, 50) of its 50 consecutive minibatches once each
         result["other_configs"] = {f"cfg{k}": run_side_config(args, z, wl, np, torch, k, link_peak, n_cores)
                                    for k in (1, 3)}
+        if not args.no_config4:
+            result["other_configs"]["cfg4"] = run_side_config(args, z, wl, np, torch, 4, link_peak, n_cores,
+                                                              n_lists=max(5, min(args.steps, 50)))
     print(json.dumps(result))
 
 
