@@ -55,6 +55,13 @@ int64_t grid_blocks(int64_t n) {
   const int64_t per_block = wave_span(n) * kWavesPerBlock;
   return (n + per_block - 1) / per_block;
 }
+// Bytes set aside for the per-bin per-block counts: room for the grid of any list of up to n
+// entries (the grid grows with n up to kMaxBlocks and never exceeds it), so that the scratch a
+// caller sized for its longest list also fits every shorter one.
+int64_t counts_bytes(int64_t n) {
+  const int64_t small_grid = (n + 256 * kWavesPerBlock - 1) / (256 * kWavesPerBlock);
+  return round_up(kMaxBins * (small_grid < kMaxBlocks ? small_grid : kMaxBlocks) * 4, kAlign);
+}
 
 // Where a pass reads its elements from.
 enum Src { SRC_LIST = 0,     // the index list itself: key = idx[i], position = i
@@ -264,8 +271,7 @@ hipError_t launch_pass(int dst, const PassIO& io, int64_t n, int64_t span, int s
 int64_t zcg_order_scratch_bytes(int64_t n_idx) {
   if (n_idx <= 0) return 0;
   // one (key32, position) buffer, the per-bin per-block counts, the bin sizes
-  return round_up(n_idx * 8, kAlign) + round_up(kMaxBins * grid_blocks(n_idx) * 4, kAlign) +
-         round_up(kMaxBins * 4, kAlign);
+  return round_up(n_idx * 8, kAlign) + counts_bytes(n_idx) + round_up(kMaxBins * 4, kAlign);
 }
 
 hipError_t zcg_order_launch(const int64_t* idx, int64_t n, int64_t n_rows, int64_t* order,
@@ -278,7 +284,7 @@ hipError_t zcg_order_launch(const int64_t* idx, int64_t n, int64_t n_rows, int64
   char* ws = static_cast<char*>(scratch);
   uint32_t* buf_a = reinterpret_cast<uint32_t*>(ws);
   uint32_t* counts = reinterpret_cast<uint32_t*>(ws + round_up(n * 8, kAlign));
-  uint32_t* totals = counts + round_up(kMaxBins * grid_blocks(n) * 4, kAlign) / 4;
+  uint32_t* totals = counts + counts_bytes(n) / 4;
   uint32_t* buf_o = reinterpret_cast<uint32_t*>(order);  // the output array is the second buffer
   const int64_t span = wave_span(n);
 

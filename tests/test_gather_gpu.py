@@ -466,6 +466,16 @@ def test_make_order_argument_checks_and_capture():
     assert e.value.status == -6
     z.make_order(idx, n_rows, order, ws_ptr, ws_bytes, n_idx=0)  # nothing to do
     assert z.order_workspace_bytes(0) == 0
+    # a workspace sized for a longer list serves every shorter one, also across the change of
+    # tiling at 2^20 entries
+    big = (1 << 20) + 1
+    big_ws = torch.empty(z.order_workspace_bytes(big), dtype=torch.uint8, device="cuda")
+    for m in (big, 1 << 20, (1 << 20) - 1, 70_000):
+        lst = torch.from_numpy(wl.uniform_indices(m, 5_000_000, seed=m)).cuda()
+        o = torch.empty(m, dtype=torch.int64, device="cuda")
+        z.make_order(lst, 5_000_000, o, big_ws, big_ws.numel())
+        torch.cuda.synchronize()
+        assert np.array_equal(o.cpu().numpy(), np.argsort(lst.cpu().numpy(), kind="stable")), m
     # the build is kernel launches only: it can be captured, and a replay follows the list
     s = torch.cuda.Stream()
     g = torch.cuda.CUDAGraph()

@@ -343,3 +343,17 @@ def test_static_order_builder_refuses_oversized_lists_before_touching_the_gpu():
     assert lib.zcg_make_order_static(0x1000, 8, 0, 0x2000, None) == z.binding.EINVAL
     assert lib.zcg_make_order_static(None, 0, 100, None, None) == 0
     assert lib.zcg_make_order_static(0x1004, 8, 100, 0x2000, None) == z.binding.EALIGN
+
+
+def test_order_workspace_never_shrinks_with_the_list():
+    """A caller (the pipeline) sizes the order builder's workspace once for its longest list: every
+    shorter list must fit, also where the builder changes its tiling (around 2^20 entries)."""
+    sizes = list(range(0, 5000, 37)) + list(range((1 << 20) - 3000, (1 << 20) + 3000, 7)) + \
+        [1 << 21, (1 << 21) + 1, 5_000_000, 50_000_000, (1 << 32) - 1]
+    prev = -1
+    for n in sorted(sizes):
+        b = z.order_workspace_bytes(n)
+        assert b >= prev and b % 256 == 0 and b >= 8 * n, n
+        assert z.gather_workspace_bytes(n) >= b + 8 * n
+        prev = b
+    assert z.order_workspace_bytes(z.STATIC_ORDER_MAX_IDX) <= 9_502_720  # the static array's size
