@@ -10,6 +10,8 @@ namespace {
 constexpr int kBlock = 256;  // 4 wavefronts of 64 lanes, as in the kernels
 constexpr int kWave = 64;
 
+int saturate_int(int64_t x) { return x > INT32_MAX ? INT32_MAX : (int)x; }  // passes of absurdly long rows
+
 int floor_pow2_divisor(uint64_t x, int cap) {  // largest power of two <= cap dividing x
   int w = cap;
   while (w > 1 && (x % (uint64_t)w) != 0) w >>= 1;
@@ -25,6 +27,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
   if (opts) o = *opts;
   if (row_bytes <= 0 || (elem != 1 && elem != 2 && elem != 4 && elem != 8) || row_bytes % elem != 0 || n_idx < 0 || !plan)
     return ZCG_EINVAL;
+  if (n_idx > INT64_MAX / row_bytes) return ZCG_EINVAL;  // the output would not fit an address space
   if (table_addr % (uintptr_t)elem != 0 || out_addr % (uintptr_t)elem != 0) return ZCG_EALIGN;
 
   // defaults
@@ -151,7 +154,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
     while (lg < 6 && ((int64_t)1 << lg) < chunks) ++lg;
     if (lg < min_lg) lg = min_lg;
     plan->log2_group = lg;
-    plan->iters = (int)((chunks + ((int64_t)1 << lg) - 1) >> lg);
+    plan->iters = saturate_int((chunks + ((int64_t)1 << lg) - 1) >> lg);
     if (plan->iters == 1) {
       const int64_t groups = (n_idx + unroll - 1) / unroll;
       want_blocks = ((groups << lg) + kBlock - 1) / kBlock;
@@ -166,7 +169,7 @@ int zcg_make_plan(int64_t row_bytes, int elem, uintptr_t table_addr, uintptr_t o
         plan->line_bytes = line;
         worst_span = row_bytes + line - w;
         chunks = (worst_span + wl - 1) / wl;
-        plan->iters = (int)((chunks + kWave - 1) / kWave);
+        plan->iters = saturate_int((chunks + kWave - 1) / kWave);
       }
       // One wavefront per row keeps only unroll * 64 * vec_bytes bytes of that row in flight
       // (measured: 0.7 GB/s per row over the host link), so a short list of long rows cannot
