@@ -15,6 +15,7 @@ namespace {
 
 std::mutex g_mu;
 std::unordered_set<const zcg_table*> g_live;
+uint64_t g_next_serial = 1;  // guarded by g_mu
 thread_local int t_last_hip = 0;
 
 int elem_of(int dtype) {
@@ -41,10 +42,12 @@ zcg_table* make_handle(int kind, int dtype, int elem, int device, void* host, vo
   if (!t) return nullptr;
   t->kind = kind; t->dtype = dtype; t->elem = elem; t->device = device;
   t->parent = parent;
+  t->parent_serial = parent ? parent->serial : 0;
   t->host_resident = parent ? parent->host_resident : kind != ZCG_KIND_DEVICE;
   t->host = host; t->dev = dev; t->n_rows = n_rows; t->dim = dim;
   t->row_bytes = dim * elem;
   std::lock_guard<std::mutex> lk(g_mu);
+  t->serial = g_next_serial++;
   g_live.insert(t);
   return t;
 }
@@ -69,8 +72,10 @@ bool zcg_is_live(const zcg_table* t) {
   if (!t) return false;
   std::lock_guard<std::mutex> lk(g_mu);
   if (g_live.count(t) == 0) return false;
-  // a view lives only as long as the table it slices
-  return t->kind != ZCG_KIND_VIEW || g_live.count(t->parent) != 0;
+  // a view lives only as long as the very table it slices: a later handle that happens to be
+  // allocated at the parent's old address has another serial
+  return t->kind != ZCG_KIND_VIEW ||
+         (g_live.count(t->parent) != 0 && t->parent->serial == t->parent_serial);
 }
 
 int zcg_fail_hip(hipError_t e) {

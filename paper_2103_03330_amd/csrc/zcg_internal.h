@@ -14,6 +14,8 @@ struct zcg_table {
   int kind;
   bool host_resident;       // the rows live in mapped host memory (read over the host link)
   const zcg_table* parent;  // VIEW: the table it slices, else nullptr
+  uint64_t serial;          // unique per handle ever made (a freed handle's address may be reused)
+  uint64_t parent_serial;   // VIEW: the serial its parent had when the view was made
   int dtype;
   int elem;  // bytes per element
   int device;

@@ -357,3 +357,26 @@ def test_order_workspace_never_shrinks_with_the_list():
         assert z.gather_workspace_bytes(n) >= b + 8 * n
         prev = b
     assert z.order_workspace_bytes(z.STATIC_ORDER_MAX_IDX) <= 9_502_720  # the static array's size
+
+
+def test_a_view_dies_with_its_parent_even_if_the_handle_address_is_reused():
+    """Views check the identity of their parent, not only its address: handles are heap objects,
+    and the allocator readily hands a freed handle's address to the next one."""
+    lib = z.load_library()
+    dead_views = []
+    for _ in range(200):
+        parent = z.table_from_device(0x7F0000000000, 1000, 16, "f32")
+        view = z.table_view(parent, 64, 10, 16, "f32")
+        assert view.device_ptr == 0x7F0000000040 and view.row_bytes == 64
+        nested = z.table_view(view, 64, 5, 16, "f32")  # a view of a view hangs off the same root
+        assert nested.device_ptr == 0x7F0000000080
+        parent.close()
+        dead_views += [view, nested]
+        fresh = z.table_from_device(0x7E0000000000, 1000, 16, "f32")  # may reuse the parent's address
+        for v in dead_views[-2:]:
+            assert lib.zcg_table_device_ptr(v.handle) is None
+            assert lib.zcg_gather(v.handle, 0x1000, 1, 0x2000, None) == z.binding.EHANDLE
+        fresh.close()
+    for v in dead_views:
+        v.close()  # a dead view can still be released, once
+        assert lib.zcg_unregister_table(v.handle or 1) == z.binding.EHANDLE
