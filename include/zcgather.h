@@ -125,7 +125,8 @@ typedef struct zcg_launch_opts {
                       rows that share a line or a 256-byte pair of lines then share a
                       link request, so the walk pays for long lists that are dense in
                       their table (decided from n_idx, n_rows and the row size).
-                      Ignored otherwise, and by every forced variant.                   */
+                      Ignored otherwise, and by every forced variant. When it is used it
+                      must not overlap the list, the table or the output (ZCG_EALIAS).  */
   int64_t workspace_bytes; /* size of workspace_dev in bytes (0 with a null pointer)       */
 } zcg_launch_opts;
 
@@ -264,7 +265,8 @@ int zcg_gather_ordered(const zcg_table* t, const int64_t* idx_dev, const int64_t
  * free to reuse once the stream has passed the call). order_dev itself is used as
  * a second buffer while the order is built. n_rows bounds the index values: only
  * the bits below it are sorted, so entries outside [0, n_rows) still yield a
- * permutation, just not an ascending one. n_idx < 2^32 (ZCG_EINVAL beyond).
+ * permutation, just not an ascending one. n_idx < 2^32 (ZCG_EINVAL beyond). The
+ * list, the order and the workspace must not overlap (ZCG_EALIAS).
  * Safe under stream capture: only kernel nodes are recorded.
  */
 int zcg_order_workspace_bytes(int64_t n_idx, int64_t* bytes);

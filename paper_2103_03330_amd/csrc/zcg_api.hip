@@ -296,6 +296,10 @@ static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64
   if (o0 < t1 && t0 < o1) return ZCG_EALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!order_dev && wants_order(t, n_idx, opts)) {
+    // the workspace is written while the list, the table and the output are in use
+    const uintptr_t w0 = (uintptr_t)opts->workspace_dev, w1 = w0 + (uintptr_t)opts->workspace_bytes;
+    const uintptr_t i0 = (uintptr_t)idx_dev, i1 = i0 + (uintptr_t)(n_idx * 8);
+    if ((w0 < o1 && o0 < w1) || (w0 < t1 && t0 < w1) || (w0 < i1 && i0 < w1)) return ZCG_EALIAS;
     // the order lives at the start of the workspace, the builder's scratch behind it
     int64_t* order = static_cast<int64_t*>(opts->workspace_dev);
     char* scratch = static_cast<char*>(opts->workspace_dev) + (n_idx * 8 + 255) / 256 * 256;

@@ -350,6 +350,10 @@ int zcg_make_order_static(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows,
   if (n_idx == 0) return ZCG_OK;
   if (!idx_dev || !order_dev) return ZCG_EINVAL;
   if (((uintptr_t)idx_dev | (uintptr_t)order_dev) % 8) return ZCG_EALIGN;
+  {
+    const uintptr_t i0 = (uintptr_t)idx_dev, o0 = (uintptr_t)order_dev, len = (uintptr_t)(n_idx * 8);
+    if (i0 < o0 + len && o0 < i0 + len) return ZCG_EALIAS;  // the order may not overwrite the list
+  }
   void* scratch = nullptr;
   hipError_t e = static_scratch(&scratch);
   if (e != hipSuccess) return zcg_fail_hip(e);
@@ -373,6 +377,12 @@ int zcg_make_order(const int64_t* idx_dev, int64_t n_idx, int64_t n_rows, int64_
   if (((uintptr_t)idx_dev | (uintptr_t)order_dev) % 8 || (uintptr_t)workspace_dev % kAlign)
     return ZCG_EALIGN;
   if (workspace_bytes < zcg_order_scratch_bytes(n_idx)) return ZCG_EINVAL;
+  {  // the list is read while the order and the workspace are written, and those two differ
+    const uintptr_t i0 = (uintptr_t)idx_dev, o0 = (uintptr_t)order_dev, w0 = (uintptr_t)workspace_dev;
+    const uintptr_t len = (uintptr_t)(n_idx * 8), w1 = w0 + (uintptr_t)workspace_bytes;
+    if ((i0 < o0 + len && o0 < i0 + len) || (i0 < w1 && w0 < i0 + len) || (o0 < w1 && w0 < o0 + len))
+      return ZCG_EALIAS;
+  }
   hipError_t e = zcg_order_launch(idx_dev, n_idx, n_rows, order_dev, workspace_dev,
                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);

@@ -552,6 +552,11 @@ def test_auto_with_lent_workspace_orders_short_rows(n_rows, dim, dtype):
         with pytest.raises(z.ZcgError) as e:
             z.gather_ex(table, idx_dev, out, z.LaunchOpts(workspace_bytes=64))
         assert e.value.status == -1
+        # a workspace that overlaps the list or the table is refused before anything is launched
+        for bad_ws in (idx_dev.data_ptr() // 256 * 256, table.device_ptr):
+            with pytest.raises(z.ZcgError) as e:
+                z.gather_ex(table, idx_dev, out, z.LaunchOpts(workspace_dev=bad_ws, workspace_bytes=ws_bytes))
+            assert e.value.status == -7
     finally:
         table.close()
 

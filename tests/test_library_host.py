@@ -380,3 +380,15 @@ def test_a_view_dies_with_its_parent_even_if_the_handle_address_is_reused():
     for v in dead_views:
         v.close()  # a dead view can still be released, once
         assert lib.zcg_unregister_table(v.handle or 1) == z.binding.EHANDLE
+
+
+def test_order_builder_refuses_overlapping_buffers():
+    lib = z.load_library()
+    n = 1000
+    ws = z.order_workspace_bytes(n)
+    idx, order, work = 0x7F0000000000, 0x7F0000100000, 0x7F0000200000
+    # nothing is launched for the bad cases: the checks come first (a good call would need a GPU)
+    assert lib.zcg_make_order(idx, n, 5000, idx + 4000, work, ws, None) == z.binding.EALIAS      # order over the list
+    assert lib.zcg_make_order(idx, n, 5000, order, idx, ws, None) == z.binding.EALIAS            # workspace over the list
+    assert lib.zcg_make_order(idx, n, 5000, work + 512, work, ws, None) == z.binding.EALIAS      # order inside the workspace
+    assert lib.zcg_make_order_static(idx, n, 5000, idx + 7992, None) == z.binding.EALIAS
