@@ -328,7 +328,9 @@ int zcg_validate_indices(const zcg_table* t, const int64_t* idx_dev, int64_t n_i
  * The DMA-based method the paper argues against (Section 4.1.2 (b)): CPU
  * threads gather the rows into a dense staging buffer, then ONE host-to-device
  * copy moves it. Reported as a baseline.
- *   idx_host       : host, n_idx int64; checked, ZCG_ERANGE on a bad entry
+ *   idx_host       : host, n_idx int64; checked while gathering, ZCG_ERANGE on a bad entry
+ *                    (out_dev then holds nothing of this call; the chunked form may
+ *                    already have copied the chunks before the bad entry)
  *   staging_pinned : host, CALLER-OWNED, >= n_idx*row_bytes bytes, should be
  *                    pinned (hipHostMalloc) for the copy to be asynchronous
  *   n_threads      : CPU threads for the gather (<=0: all available)

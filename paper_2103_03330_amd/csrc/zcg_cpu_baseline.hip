@@ -4,6 +4,7 @@
 // start-up out of the timed region.
 #include <hip/hip_runtime_api.h>
 
+#include <atomic>
 #include <condition_variable>
 #include <cstring>
 #include <functional>
@@ -102,14 +103,26 @@ int resolve_threads(int n_threads) {
   return hc ? (int)hc : 1;
 }
 
-void gather_rows_cpu(const char* table, int64_t row_bytes, const int64_t* idx, int64_t lo,
-                     int64_t hi, char* staging, int n_threads) {
+// Rows [lo, hi) of the list into the staging buffer, split evenly over the threads. Every thread
+// checks the indices it is about to use (so the check costs no pass of its own over the list);
+// returns false, with some rows not gathered, if any index is outside [0, n_rows).
+bool gather_rows_cpu(const char* table, int64_t n_rows, int64_t row_bytes, const int64_t* idx,
+                     int64_t lo, int64_t hi, char* staging, int n_threads) {
+  std::atomic<bool> bad(false);
+  std::atomic<bool>* bad_p = &bad;
   pool().run(n_threads, [=](int t, int n) {
     const int64_t span = hi - lo;
     const int64_t a = lo + span * t / n, b = lo + span * (t + 1) / n;
-    for (int64_t i = a; i < b; ++i)
-      std::memcpy(staging + i * row_bytes, table + idx[i] * row_bytes, (size_t)row_bytes);
+    for (int64_t i = a; i < b; ++i) {
+      const int64_t r = idx[i];
+      if (r < 0 || r >= n_rows) {
+        bad_p->store(true, std::memory_order_relaxed);
+        return;
+      }
+      std::memcpy(staging + i * row_bytes, table + r * row_bytes, (size_t)row_bytes);
+    }
   });
+  return !bad.load();
 }
 
 int check_call(const zcg_table* t, const int64_t* idx_host, int64_t n_idx, void* staging,
@@ -118,8 +131,6 @@ int check_call(const zcg_table* t, const int64_t* idx_host, int64_t n_idx, void*
   if (!t->host_resident || !t->host) return ZCG_EINVAL;
   if (n_idx < 0) return ZCG_EINVAL;
   if (n_idx > 0 && (!idx_host || !staging || !out_dev)) return ZCG_EINVAL;
-  for (int64_t i = 0; i < n_idx; ++i)
-    if (idx_host[i] < 0 || idx_host[i] >= t->n_rows) return ZCG_ERANGE;
   return ZCG_OK;
 }
 
@@ -131,8 +142,9 @@ int zcg_cpu_gather_memcpy(const zcg_table* t, const int64_t* idx_host, int64_t n
                           void* staging_pinned, void* out_dev, int n_threads, void* stream) {
   int rc = check_call(t, idx_host, n_idx, staging_pinned, out_dev);
   if (rc || n_idx == 0) return rc;
-  gather_rows_cpu(static_cast<const char*>(t->host), t->row_bytes, idx_host, 0, n_idx,
-                  static_cast<char*>(staging_pinned), resolve_threads(n_threads));
+  if (!gather_rows_cpu(static_cast<const char*>(t->host), t->n_rows, t->row_bytes, idx_host, 0, n_idx,
+                       static_cast<char*>(staging_pinned), resolve_threads(n_threads)))
+    return ZCG_ERANGE;  // nothing has been copied to the GPU
   hipError_t e = hipMemcpyAsync(out_dev, staging_pinned, (size_t)(n_idx * t->row_bytes),
                                 hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);
@@ -149,7 +161,9 @@ int zcg_cpu_gather_memcpy_chunked(const zcg_table* t, const int64_t* idx_host, i
   char* out = static_cast<char*>(out_dev);
   for (int64_t lo = 0; lo < n_idx; lo += chunk_rows) {
     const int64_t hi = lo + chunk_rows < n_idx ? lo + chunk_rows : n_idx;
-    gather_rows_cpu(static_cast<const char*>(t->host), t->row_bytes, idx_host, lo, hi, staging, nt);
+    if (!gather_rows_cpu(static_cast<const char*>(t->host), t->n_rows, t->row_bytes, idx_host, lo, hi,
+                         staging, nt))
+      return ZCG_ERANGE;  // earlier chunks may already be on their way to the GPU
     // the copy of this chunk runs while the CPU gathers the next one
     hipError_t e = hipMemcpyAsync(out + lo * t->row_bytes, staging + lo * t->row_bytes,
                                   (size_t)((hi - lo) * t->row_bytes), hipMemcpyHostToDevice,

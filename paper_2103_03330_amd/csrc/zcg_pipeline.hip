@@ -99,8 +99,14 @@ bool wait_for(zcg_pipeline* p, std::unique_lock<std::mutex>& lk, int timeout_ms,
 int submit_impl(zcg_pipeline* p, const int64_t* idx_host, int64_t n_idx, int timeout_ms, int* slot) {
   if (!p || !slot || n_idx < 0 || n_idx > p->max_rows || (n_idx > 0 && !idx_host)) return ZCG_EINVAL;
   if (!zcg_is_live(p->table)) return ZCG_EHANDLE;
-  for (int64_t i = 0; i < n_idx; ++i)
-    if (idx_host[i] < 0 || idx_host[i] >= p->table->n_rows) return ZCG_ERANGE;
+  {  // one branch-free pass (vectorises): the smallest and the largest entry decide
+    int64_t lo = 0, hi = 0;
+    for (int64_t i = 0; i < n_idx; ++i) {
+      lo = idx_host[i] < lo ? idx_host[i] : lo;
+      hi = idx_host[i] > hi ? idx_host[i] : hi;
+    }
+    if (lo < 0 || hi >= p->table->n_rows) return ZCG_ERANGE;
+  }
   int k;
   bool wait_copy, wait_release;
   {
