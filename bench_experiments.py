@@ -172,13 +172,19 @@ def run_align_sweep(args, z, wl, np, torch, link_peak):
             pt[name + "_gbps"] = round(rows * rb / tot_ms / 1e6, 2)
             pt[name + "_frac"] = round(rows * rb / tot_ms / 1e6 / link_peak, 4)
         staging = z.pinned_alloc(out.numel() * 4)
-        t0, rows = time.perf_counter(), 0
-        for b in range(len(lists)):
-            z.cpu_gather_memcpy_chunked(table, lists[b], staging, out, max(1024, (4 << 20) // rb),
-                                        wl.default_threads(), stream)
+        for name, fn in (("dma_one_shot_gbps", lambda b: z.cpu_gather_memcpy(
+                              table, lists[b], staging, out, wl.default_threads(), stream)),
+                         ("dma_chunked_gbps", lambda b: z.cpu_gather_memcpy_chunked(
+                              table, lists[b], staging, out, max(1024, (4 << 20) // rb),
+                              wl.default_threads(), stream))):
+            fn(len(lists) - 1)  # warm-up: first touch of the staging pages
             torch.cuda.synchronize()
-            rows += lists[b].size
-        pt["dma_chunked_gbps"] = round(rows * rb / (time.perf_counter() - t0) / 1e9, 2)
+            t0, rows = time.perf_counter(), 0
+            for b in range(len(lists)):
+                fn(b)
+                torch.cuda.synchronize()
+                rows += lists[b].size
+            pt[name] = round(rows * rb / (time.perf_counter() - t0) / 1e9, 2)
         z.pinned_free(staging)
         pt["plan_auto"] = z.VARIANT_NAMES[z.plan_gather(table, lists[0].size, out)["variant"]]
         table.close()

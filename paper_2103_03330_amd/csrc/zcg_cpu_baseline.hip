@@ -113,11 +113,20 @@ bool gather_rows_cpu(const char* table, int64_t n_rows, int64_t row_bytes, const
   pool().run(n_threads, [=](int t, int n) {
     const int64_t span = hi - lo;
     const int64_t a = lo + span * t / n, b = lo + span * (t + 1) / n;
+    constexpr int64_t kAhead = 12;  // rows whose first lines are requested ahead of their copy
     for (int64_t i = a; i < b; ++i) {
       const int64_t r = idx[i];
       if (r < 0 || r >= n_rows) {
         bad_p->store(true, std::memory_order_relaxed);
         return;
+      }
+      if (i + kAhead < b) {
+        const int64_t ra = idx[i + kAhead];
+        if (ra >= 0 && ra < n_rows) {
+          const char* p = table + ra * row_bytes;
+          __builtin_prefetch(p, 0, 0);
+          if (row_bytes > 64) __builtin_prefetch(p + 64, 0, 0);
+        }
       }
       std::memcpy(staging + i * row_bytes, table + r * row_bytes, (size_t)row_bytes);
     }
