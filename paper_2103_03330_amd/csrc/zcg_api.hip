@@ -295,11 +295,20 @@ static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64
   const uintptr_t t0 = (uintptr_t)t->dev, t1 = t0 + (uintptr_t)(t->n_rows * t->row_bytes);
   if (o0 < t1 && t0 < o1) return ZCG_EALIAS;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!order_dev && wants_order(t, n_idx, opts)) {
+  const bool build_order = !order_dev && wants_order(t, n_idx, opts);
+  if (build_order) {
     // the workspace is written while the list, the table and the output are in use
     const uintptr_t w0 = (uintptr_t)opts->workspace_dev, w1 = w0 + (uintptr_t)opts->workspace_bytes;
     const uintptr_t i0 = (uintptr_t)idx_dev, i1 = i0 + (uintptr_t)(n_idx * 8);
     if ((w0 < o1 && o0 < w1) || (w0 < t1 && t0 < w1) || (w0 < i1 && i0 < w1)) return ZCG_EALIAS;
+  }
+  // every argument check comes before the first launch
+  zcg_plan plan;
+  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, t->host_resident,
+                         order_dev != nullptr || build_order, opts, &plan);
+  if (rc) return rc;
+  if ((order_dev || build_order) && plan.variant == ZCG_VARIANT_NAIVE) return ZCG_EINVAL;
+  if (build_order) {
     // the order lives at the start of the workspace, the builder's scratch behind it
     int64_t* order = static_cast<int64_t*>(opts->workspace_dev);
     char* scratch = static_cast<char*>(opts->workspace_dev) + (n_idx * 8 + 255) / 256 * 256;
@@ -307,11 +316,6 @@ static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64
     if (e != hipSuccess) return zcg_fail_hip(e);
     order_dev = order;
   }
-  zcg_plan plan;
-  int rc = zcg_make_plan(t->row_bytes, t->elem, t0, o0, n_idx, t->host_resident, order_dev != nullptr,
-                         opts, &plan);
-  if (rc) return rc;
-  if (order_dev && plan.variant == ZCG_VARIANT_NAIVE) return ZCG_EINVAL;
   hipError_t e = zcg_launch_gather(plan, t->dev, idx_dev, order_dev, n_idx, out_dev, t->row_bytes,
                                    t->elem, s);
   return e == hipSuccess ? ZCG_OK : zcg_fail_hip(e);

@@ -552,6 +552,13 @@ def test_auto_with_lent_workspace_orders_short_rows(n_rows, dim, dtype):
         with pytest.raises(z.ZcgError) as e:
             z.gather_ex(table, idx_dev, out, z.LaunchOpts(workspace_bytes=64))
         assert e.value.status == -1
+        # a bad option is refused before the order builder touches the workspace
+        ws.zero_()
+        with pytest.raises(z.ZcgError) as e:
+            z.gather_ex(table, idx_dev, out, z.LaunchOpts(workspace_dev=ws_ptr, workspace_bytes=ws_bytes, unroll=3))
+        assert e.value.status == -1
+        torch.cuda.synchronize()
+        assert not bool(ws.any())
         # a workspace that overlaps the list or the table is refused before anything is launched
         for bad_ws in (idx_dev.data_ptr() // 256 * 256, table.device_ptr):
             with pytest.raises(z.ZcgError) as e:
