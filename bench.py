@@ -169,7 +169,7 @@ def main():
     ap.add_argument("--max-table-gb", type=float, default=200.0)
     ap.add_argument("--no-baselines", action="store_true", help="skip the CPU legs (for profiling)")
     ap.add_argument("--pipeline-mode", default="all",
-                    choices=["all", "serial", "nomask", "mask8", "mask16", "mask24", "threads"],
+                    choices=["all", "serial", "ring", "nomask", "mask8", "mask16", "mask24", "threads"],
                     help="config 8: run one mode only (for kernel-trace profiles)")
     ap.add_argument("--only-point", default="",
                     help="config 5: run one point only, by name (e.g. cfg5_f16_d16; for kernel-trace profiles)")

@@ -365,6 +365,33 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
             cs.close()
         return ms
 
+    def ring_alone(n_buffers):
+        """Nothing but the ring: the consumer takes each buffer and lets go of it at once, so the
+        gather bounds the loop and whatever the ring adds to the kernel's own time shows."""
+        rb_bufs = bufs if n_buffers == 2 else bufs + [torch.empty_like(bufs[0]) for _ in range(n_buffers - 2)]
+        cons = torch.cuda.Stream()
+        pipe = z.pipeline_create(table, max_rows, rb_bufs, None)
+        for i in range(n_buffers):  # warm-up: every slot used once
+            s0 = pipe.submit(lists[i % 16])
+            pipe.acquire(s0, cons)
+            pipe.release(s0, cons)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        pending = []
+        for i in range(reps):
+            pending.append(pipe.submit(lists[i % 16], timeout_ms=10_000))
+            if len(pending) == n_buffers:
+                s0 = pending.pop(0)
+                pipe.acquire(s0, cons)
+                pipe.release(s0, cons)
+        for s0 in pending:
+            pipe.acquire(s0, cons)
+            pipe.release(s0, cons)
+        cons.synchronize()
+        ms = (time.perf_counter() - t) / reps * 1e3
+        pipe.close()
+        return ms
+
     # The same with the sampler inside the loop (Section 3.3: sampling, gathering and training are
     # three stages; the first two run beside the third). Lists are drawn live from the graph.
     def sampler_graph():
@@ -479,6 +506,12 @@ def run_pipeline(args, z, wl, np, torch, link_peak):
                       "ms_per_minibatch": round(threaded(16), 3)})
         cases.append({"mode": f"4 sampler threads -> producer thread | consumer thread, 2 buffers, gather on 16 CUs / compute on {n_cus - 16}",
                       "ms_per_minibatch": round(threaded(16, 4), 3)})
+    if only in ("all", "ring"):
+        rows_avg = float(np.mean([lists[i % 16].size for i in range(reps)]))
+        for nb in (2, 3):
+            ms = ring_alone(nb)
+            cases.append({"mode": f"ring alone (no consumer work), {nb} buffers", "ms_per_minibatch": round(ms, 4),
+                          "gathered_GBps": round(rows_avg * rb / ms / 1e6, 2)})
     if only in ("all", "nomask"):
         cases.append({"mode": "pipeline, 2 buffers, no masks", "ms_per_minibatch": round(pipelined(0), 3)})
     for n in (8, 16, 24):

@@ -375,7 +375,9 @@ int zcg_device_cu_count(int device, int* n_cus);
  *   gather_stream : stream the list copies and gathers run on (e.g. one from
  *                   zcg_stream_create_cu_mask); NULL = the pipeline creates its own
  * The pipeline owns, per buffer, a pinned staging area and a device copy of the
- * index list (max_rows int64 each). For host-resident tables with rows of at
+ * index list (max_rows int64 each). For tables of at most 2^32 rows the list is
+ * staged as 32-bit values that a small kernel on the gather stream reads straight
+ * from the staging area and widens (half the bytes over the link, no copy engine). For host-resident tables with rows of at
  * most 128 bytes it also owns the memory of zcg_make_order and gathers lists
  * that are long and dense enough in the table in ascending table order (same
  * result, fewer link requests). Threads: ONE producer thread (submit,
@@ -387,7 +389,7 @@ typedef struct zcg_pipeline zcg_pipeline;
 int zcg_pipeline_create(const zcg_table* t, int64_t max_rows, int n_buffers, void* const* out_bufs,
                         void* gather_stream, zcg_pipeline** out);
 /*
- * Producer: copy the list (host, checked: ZCG_ERANGE) to the GPU by DMA and enqueue
+ * Producer: stage the list (host, checked: ZCG_ERANGE), bring it to the GPU and enqueue
  * the gather into the next buffer of the ring, behind the consumer's release of
  * that buffer. Returns at once unless the producer is a whole ring ahead of its own
  * list copies. *slot receives the buffer number. ZCG_EBUSY if the consumer has not

@@ -207,3 +207,41 @@ def test_ring_sorts_short_rows_by_itself():
             torch.cuda.synchronize()
             pipe.close()
             table.close()
+
+
+@pytest.mark.parametrize("extra_rows", [0, 4096])
+def test_lists_cross_the_link_narrow_up_to_2_32_rows_and_wide_beyond(extra_rows):
+    """Row numbers of a table of at most 2^32 rows are staged and copied as 32-bit values and widened
+    on the GPU (the largest, 2^32 - 1, included); one more row and the list travels as int64."""
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    torch.cuda.set_device(0)
+    n_rows = (1 << 32) + extra_rows
+    table = z.alloc_table(n_rows, 1, "i8")  # 4.3 GB of one-byte rows
+    try:
+        host = table.host_array()
+        rng = np.random.default_rng(77 + extra_rows)
+        regions = [(0, 5000), ((1 << 31) - 3000, (1 << 31) + 3000), (n_rows - 6000, n_rows)]
+        parts = []
+        for lo, hi in regions:
+            host[lo:hi, 0] = rng.integers(-128, 128, hi - lo, dtype=np.int8)
+            parts.append(rng.integers(lo, hi, 4000, dtype=np.int64))
+        parts.append(np.array([0, n_rows - 1, (1 << 32) - 1, 1 << 31], dtype=np.int64))
+        idx = rng.permutation(np.concatenate(parts))
+        bufs = [torch.zeros((idx.size, 1), dtype=torch.int8, device="cuda") for _ in range(2)]
+        pipe = z.pipeline_create(table, idx.size, bufs)
+        try:
+            for lst in (idx, idx[::-1].copy(), idx[:1]):
+                slot = pipe.submit(lst)
+                buf, n = pipe.acquire(slot)
+                torch.cuda.synchronize()
+                assert n == lst.size
+                assert buf[:n].cpu().numpy().tobytes() == oracle_gather(host, lst).tobytes()
+                pipe.release(slot)
+            with pytest.raises(Exception):
+                pipe.submit(np.array([n_rows], dtype=np.int64))
+        finally:
+            torch.cuda.synchronize()
+            pipe.close()
+    finally:
+        table.close()
