@@ -158,7 +158,8 @@ def main():
                     help="workload 1..4 (default 2, the metric's); 5 = width/dtype sweep; "
                          "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning; "
                          "8 = producer/consumer pipeline; 9 = list-length sweep; "
-                         "10 = fixed launch sequence for the link request counters")
+                         "10 = fixed launch sequence for the link request counters; "
+                         "11 = request rate against table size")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
     ap.add_argument("--variant", type=int, default=0,
                     help="force a kernel (ablation; configs 1-5): 1 naive, 2 rowvec, 3 aligned, 4 halfline")
@@ -191,7 +192,7 @@ def main():
     import paper_2103_03330_amd as z
     import zcg_workload as wl
     from bench_experiments import (run_align_sweep, run_list_length, run_pipeline, run_provisioning,
-                                   run_request_blocks, run_request_sequence, run_sweep)
+                                   run_request_blocks, run_request_sequence, run_sweep, run_table_size)
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -203,6 +204,11 @@ def main():
 
     if args.config == 10:  # no probes here: the profiler should see the gather kernels only
         print(json.dumps({"request_sequence": run_request_sequence(args, z, wl, np, torch)}))
+        return
+    if args.config == 11:
+        print(json.dumps({"config": {"workload": "1,000,000 uniform random rows of 128 and 512 bytes out of mapped "
+                                                 "tables of 0.13 ... 51 GB"},
+                          "table_size_sweep": run_table_size(args, z, wl, np, torch)}))
         return
     link_peak = probe.measure_h2d(1 << 30, 10)
     nominal, link_name = nominal_link_gbps()

@@ -688,3 +688,37 @@ def run_list_length(args, z, wl, np, torch, link_peak):
             print(f"# {pt}", file=sys.stderr, flush=True)
         table.close()
     return pts
+
+
+def run_table_size(args, z, wl, np, torch):
+    """Does the link's request limit depend on how much memory the table spans? 1,000,000 uniform
+    random rows of 128 bytes (one read request each) and of 512 bytes (bound by bytes) out of mapped
+    tables of 0.13 ... 51 GB. The tables are left as allocated: only the rate matters here."""
+    cur = torch.cuda.current_stream()
+    n_idx = 1_000_000
+    pts = []
+    for dim, sizes in ((32, (1_000_000, 10_000_000, 100_000_000, 400_000_000)), (128, (10_000_000, 100_000_000))):
+        for n_rows in sizes:
+            if n_rows * dim * 4 > args.max_table_gb * 1e9:
+                continue
+            table = z.alloc_table(n_rows, dim, "f32")
+            lists = [torch.from_numpy(wl.uniform_indices(n_idx, n_rows, seed=b)).cuda() for b in range(4)]
+            out = torch.empty((n_idx, dim), dtype=torch.float32, device="cuda")
+            for i in range(3):
+                z.gather(table, lists[i % 4], out, stream=cur)
+            torch.cuda.synchronize()
+            ms = []
+            for i in range(max(12, min(args.steps, 40))):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(cur)
+                z.gather(table, lists[i % 4], out, stream=cur)
+                e1.record(cur)
+                e1.synchronize()
+                ms.append(e0.elapsed_time(e1))
+            m = float(np.median(ms))
+            pt = {"row_bytes": dim * 4, "table_gb": round(n_rows * dim * 4 / 1e9, 2),
+                  "rows_per_s_M": round(n_idx / m / 1e3, 1), "gbps": round(n_idx * dim * 4 / m / 1e6, 2)}
+            pts.append(pt)
+            print(f"# {pt}", file=sys.stderr, flush=True)
+            table.close()
+    return pts
