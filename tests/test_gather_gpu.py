@@ -707,3 +707,35 @@ def test_very_wide_rows_and_first_last_row(n_rows, dim, dtype):
             assert_same_bits(out, want, f"ordered {dtype} dim={dim} n_idx={len(idx)}")
     finally:
         table.close()
+
+
+@pytest.mark.parametrize("resident", ["host", "hbm"])
+def test_lists_of_more_than_2_31_entries(resident):
+    """Positions in the list beyond 2^31 and 2^32 output bytes: 2^31 + 70,001 two-byte rows (a
+    17 GB list held in HBM). Checked against the oracle on three stretches of a million entries
+    (first, last, around 2^31) and, as a property over every entry, against the library's own
+    indexing of the same table in chunks."""
+    n_rows, dim, n_idx = 60_000, 1, (1 << 31) + 70_001
+    host = host_table(n_rows, dim, "f16", seed=91, mode=wl.FILL_RAW_BITS)
+    table_np = host.host_array().copy()
+    dev_copy = torch.from_numpy(table_np).cuda()
+    table = host if resident == "host" else z.table_from_device(dev_copy.data_ptr(), n_rows, dim, "f16")
+    try:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(20310331)
+        idx = torch.randint(0, n_rows, (n_idx,), dtype=torch.int64, device="cuda", generator=gen)
+        idx[0], idx[-1], idx[1 << 31] = n_rows - 1, 0, n_rows - 1
+        out = torch.full((n_idx, dim), -7, dtype=torch.float16, device="cuda")
+        z.gather(table, idx, out)
+        torch.cuda.synchronize()
+        for lo in (0, (1 << 31) - 500_000, n_idx - 1_000_000):
+            part = idx[lo:lo + 1_000_000].cpu().numpy()
+            assert_same_bits(out[lo:lo + 1_000_000], oracle_gather(table_np, part), f"entries from {lo}")
+        bits, table_bits = out.view(torch.int16).view(-1), dev_copy.view(torch.int16).view(-1)
+        step = 1 << 28
+        for lo in range(0, n_idx, step):
+            assert torch.equal(bits[lo:lo + step], table_bits[idx[lo:lo + step]]), f"chunk at {lo}"
+    finally:
+        if table is not host:
+            table.close()
+        host.close()
