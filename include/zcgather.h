@@ -159,6 +159,10 @@ int zcg_last_hip_error(void); /* hipError_t of the last failed HIP call on this 
  * unmoved until zcg_unregister_table. Pins with hipHostRegister (mapped,
  * portable) on `device`. Errors: ZCG_EINVAL (null, n_rows<=0, dim<=0),
  * ZCG_EDTYPE, ZCG_EALIGN, ZCG_EHIP (pin or map refused; nothing stays pinned).
+ * Some installations refuse hipHostRegister for memory that already exists (the
+ * machines this library was measured on do: there this call returns ZCG_EHIP and
+ * has only had its argument checks exercised); zcg_alloc_table always works, and
+ * zcg_table_view gives tables that start anywhere inside such an allocation.
  */
 int zcg_register_table(void* host_ptr, int64_t n_rows, int64_t dim, int dtype, int device,
                        zcg_table** out);
