@@ -36,7 +36,7 @@ extern "C" {
 #define ZCG_EHIP (-4)    /* a HIP runtime call failed; see zcg_last_hip_error() */
 #define ZCG_ENOMEM (-5)  /* host allocation failed                              */
 #define ZCG_EALIGN (-6)  /* pointer not aligned to the element size             */
-#define ZCG_EALIAS (-7)  /* output range overlaps the table                     */
+#define ZCG_EALIAS (-7)  /* ranges that must be distinct overlap (output/table ...) */
 #define ZCG_ERANGE (-8)  /* an index is outside [0, n_rows) (host-side checks)  */
 #define ZCG_EBUSY (-9)   /* pipeline: the next buffer has not been released yet */
 #define ZCG_ETIMEDOUT (-10) /* pipeline: a bounded wait ran out                   */
@@ -223,7 +223,8 @@ int zcg_unregister_table(zcg_table* t);
  *             list is then fetched over the link too, 8 bytes per row).
  *   out_dev : device, CALLER-OWNED, n_idx*row_bytes bytes, aligned to the
  *             element size (16-byte alignment enables the widest accesses),
- *             must not overlap the table (ZCG_EALIAS).
+ *             must not overlap the table, the list or a caller's order
+ *             (ZCG_EALIAS).
  * The caller keeps idx_dev, out_dev and the table alive until the stream has
  * passed the kernel. n_idx == 0 succeeds without a launch. The table must not
  * change while a gather that reads it runs; rows the host rewrites after a

@@ -120,7 +120,7 @@ const char* zcg_strerror(int status) {
     case ZCG_EHIP: return "HIP runtime call failed";
     case ZCG_ENOMEM: return "out of host memory";
     case ZCG_EALIGN: return "pointer not aligned to the element size";
-    case ZCG_EALIAS: return "output overlaps the table";
+    case ZCG_EALIAS: return "ranges that must be distinct overlap (output, table, list, order or workspace)";
     case ZCG_ERANGE: return "index out of range";
     case ZCG_EBUSY: return "buffer not released by the consumer";
     case ZCG_ETIMEDOUT: return "wait timed out";
@@ -294,6 +294,11 @@ static int gather_common(const zcg_table* t, const int64_t* idx_dev, const int64
   const uintptr_t o0 = (uintptr_t)out_dev, o1 = o0 + (uintptr_t)(n_idx * t->row_bytes);
   const uintptr_t t0 = (uintptr_t)t->dev, t1 = t0 + (uintptr_t)(t->n_rows * t->row_bytes);
   if (o0 < t1 && t0 < o1) return ZCG_EALIAS;
+  {  // the list and a caller's order are read while the output is written
+    const uintptr_t i0 = (uintptr_t)idx_dev, r0 = (uintptr_t)order_dev, len = (uintptr_t)(n_idx * 8);
+    if (i0 < o1 && o0 < i0 + len) return ZCG_EALIAS;
+    if (order_dev && r0 < o1 && o0 < r0 + len) return ZCG_EALIAS;
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   const bool build_order = !order_dev && wants_order(t, n_idx, opts);
   if (build_order) {

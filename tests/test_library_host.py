@@ -104,6 +104,10 @@ def test_gather_rejects_before_launch():
         # output overlapping the table's [0x100000, 0x100000 + 10000)
         assert lib.zcg_gather(t.handle, 0x800000, 5, 0x100000 + 9996, None) == z.binding.EALIAS
         assert lib.zcg_gather(t.handle, 0x800000, 5, 0x100000 - 400, None) == z.binding.EALIAS
+        # output over the index list [0x800000, +40) or over a caller's order
+        assert lib.zcg_gather(t.handle, 0x800000, 5, 0x800000 + 36, None) == z.binding.EALIAS
+        assert lib.zcg_gather(t.handle, 0x800000, 5, 0x800000 - 496, None) == z.binding.EALIAS
+        assert lib.zcg_gather_ordered(t.handle, 0x800000, 0xA00000, 5, 0xA00000 + 32, None, None) == z.binding.EALIAS
         assert lib.zcg_gather_variant(t.handle, 0x800000, 5, 0x900000, None, 9) == z.binding.EINVAL
     finally:
         t.close()
