@@ -644,6 +644,82 @@ def test_seeded_random_shapes_knobs_and_offsets():
             backing.close()
 
 
+def test_seeded_random_cases_on_host_resident_views_hbm_copies_and_lent_workspace():
+    """400 seeded random cases: element size, row length (up to 280 KB), list length, table and
+    output offsets, where the table lives (a host-resident view, the same memory flagged as a
+    device table, a copy in HBM), default or random launch options, a caller's order or lent
+    workspace; every output byte against the oracle, guard elements around the output."""
+    rng = np.random.default_rng(20210304)
+    as_int = {1: torch.int8, 2: torch.int16, 4: torch.int32, 8: torch.int64}
+    for ci in range(400):
+        dtype = str(rng.choice(["f16", "f32", "f32", "i8", "f64"]))
+        elem = {"i8": 1, "f16": 2, "f32": 4, "f64": 8}[dtype]
+        r = rng.random()
+        dim = int(rng.integers(1, 200)) if r < 0.5 else (int(rng.integers(1, 1400)) if r < 0.9 else
+                                                         int(rng.choice([4096, 5000, 16384, 20001, 70000])))
+        n_rows = int(rng.integers(1, 3000)) if dim < 3000 else int(rng.integers(1, 60))
+        n_idx = (int(rng.choice([1, 2, 3, 63, 64, 65, 127, 129, 1000, 4097, 30000, 70000])) if dim < 3000
+                 else int(rng.choice([1, 2, 5, 33, 100])))
+        t_off = int(rng.integers(0, 70)) * elem if rng.random() < 0.7 else 0
+        o_off = int(rng.integers(0, 40)) * elem if rng.random() < 0.7 else 0
+        mode = str(rng.choice(["view", "device table over host memory", "hbm"]))
+        pad_rows = (t_off + dim * elem - 1) // (dim * elem) + 1
+        backing = z.alloc_table(n_rows + pad_rows, dim, dtype)
+        view = None
+        try:
+            wl.fill_table_ptr(backing.host_ptr, n_rows + pad_rows, dim, dtype, seed=ci, mode=wl.FILL_RAW_BITS)
+            flat = backing.host_array().reshape(-1)
+            sub = np.ascontiguousarray(flat[t_off // elem: t_off // elem + n_rows * dim].reshape(n_rows, dim))
+            if mode == "view":
+                view = z.table_view(backing, t_off, n_rows, dim, dtype)
+            elif mode == "hbm":
+                keep = torch.zeros(n_rows * dim + 80, dtype=TORCH_DT[dtype], device="cuda")
+                keep[t_off // elem: t_off // elem + n_rows * dim] = torch.from_numpy(sub.reshape(-1)).cuda()
+                view = z.table_from_device(keep.data_ptr() + t_off, n_rows, dim, dtype)
+            else:
+                view = z.table_from_device(backing.device_ptr + t_off, n_rows, dim, dtype)
+            idx = rng.integers(0, n_rows, n_idx)
+            if rng.random() < 0.2:
+                idx = np.sort(idx)
+            want = oracle_gather(sub, idx)
+            idx_dev = torch.from_numpy(idx).cuda()
+            buf = torch.zeros(n_idx * dim + 64, dtype=TORCH_DT[dtype], device="cuda")
+            out = buf[o_off // elem: o_off // elem + n_idx * dim].view(n_idx, dim)
+            opts = z.LaunchOpts()
+            if rng.random() < 0.55:
+                opts = z.LaunchOpts(variant=int(rng.integers(0, 5)), unroll=int(rng.choice([0, 1, 2, 4, 8])),
+                                    line_bytes=int(rng.choice([0, 32, 64, 128, 256])),
+                                    vec_bytes=int(rng.choice([0] + [v for v in (1, 2, 4, 8, 16) if v >= elem])),
+                                    group_lanes=int(rng.choice([0, 1, 2, 4, 8, 16, 32, 64])),
+                                    shifted_stores=int(rng.integers(0, 3)), nt_loads=int(rng.integers(0, 4)),
+                                    nt_stores=int(rng.integers(0, 3)),
+                                    max_blocks=int(rng.choice([0, 1, 7, 300, 5000])),
+                                    row_splits=int(rng.choice([0, 1, 2, 5, 64])), half_ends=int(rng.integers(0, 3)))
+            what = (f"case {ci}: {dtype} dim={dim} rows={n_rows} n_idx={n_idx} t_off={t_off} o_off={o_off} "
+                    f"{mode} opts={[getattr(opts, f) for f, _ in opts._fields_][:11]}")
+            r = rng.random()
+            if r < 0.3 and opts.variant != z.VARIANT_NAIVE:
+                z.gather_ordered(view, idx_dev, torch.randperm(n_idx, device="cuda"), out, opts)
+                what += " with an order"
+            elif r < 0.5 and opts.variant == z.VARIANT_AUTO:
+                ws_bytes = z.gather_workspace_bytes(n_idx)
+                ws = torch.zeros(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+                opts.workspace_dev = ws.data_ptr() + (-ws.data_ptr()) % 256
+                opts.workspace_bytes = ws_bytes
+                z.gather_ex(view, idx_dev, out, opts)
+                what += " with lent workspace"
+            else:
+                z.gather_ex(view, idx_dev, out, opts)
+            torch.cuda.synchronize()
+            assert_same_bits(out, want, what)
+            assert not bool(buf[: o_off // elem].view(as_int[elem]).any()), what
+            assert not bool(buf[o_off // elem + n_idx * dim:].view(as_int[elem]).any()), what
+        finally:
+            if view is not None:
+                view.close()
+            backing.close()
+
+
 def test_link_probes_give_sane_numbers():
     rtt = probe.measure_host_read_latency(4000)
     assert 0.2 < rtt < 50.0  # microseconds per dependent read of mapped host memory
