@@ -159,7 +159,8 @@ def main():
                          "6 = alignment sweep, rows of 1024..1044 bytes; 7 = resource provisioning; "
                          "8 = producer/consumer pipeline; 9 = list-length sweep; "
                          "10 = fixed launch sequence for the link request counters; "
-                         "11 = request rate against table size")
+                         "11 = request rate against table size; "
+                         "12 = the HBM-resident variant against a plain device copy")
     ap.add_argument("--batches", type=int, default=0, help="distinct minibatches cycled (0: per config)")
     ap.add_argument("--variant", type=int, default=0,
                     help="force a kernel (ablation; configs 1-5): 1 naive, 2 rowvec, 3 aligned, 4 halfline")
@@ -192,7 +193,8 @@ def main():
     import paper_2103_03330_amd as z
     import zcg_workload as wl
     from bench_experiments import (run_align_sweep, run_list_length, run_pipeline, run_provisioning,
-                                   run_request_blocks, run_request_sequence, run_sweep, run_table_size)
+                                   run_hbm_variant, run_request_blocks, run_request_sequence, run_sweep,
+                                   run_table_size)
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -209,6 +211,11 @@ def main():
         print(json.dumps({"config": {"workload": "1,000,000 uniform random rows of 128 and 512 bytes out of mapped "
                                                  "tables of 0.13 ... 51 GB"},
                           "table_size_sweep": run_table_size(args, z, wl, np, torch)}))
+        return
+    if args.config == 12:
+        print(json.dumps({"config": {"workload": "HBM-resident tables of 32 ... 4,096-byte rows, 1 M / 4 M uniform random "
+                                                 "indices, beside a plain device copy"},
+                          "hbm_variant": run_hbm_variant(args, z, wl, np, torch)}))
         return
     link_peak = probe.measure_h2d(1 << 30, 10)
     nominal, link_name = nominal_link_gbps()

@@ -722,3 +722,55 @@ def run_table_size(args, z, wl, np, torch):
             print(f"# {pt}", file=sys.stderr, flush=True)
             table.close()
     return pts
+
+
+def run_hbm_variant(args, z, wl, np, torch):
+    """The all-in-GPU comparison variant (Section 4.1.2) against its own roofline: the same gather
+    kernels on a table in HBM, with outputs far larger than the last-level cache, beside a plain
+    device-to-device copy kernel of known size (what this chip's HBM sustains for read + write) and
+    the framework's own row indexing."""
+    cur = torch.cuda.current_stream()
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(max(10, min(args.steps, 30))):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(cur)
+            fn()
+            e1.record(cur)
+            e1.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        return float(np.median(ms))
+
+    copies = []
+    for gib in (0.5, 2, 8):
+        n = int(gib * (1 << 30))
+        a = torch.empty(n, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        ms = timed(lambda: probe.device_copy(b, a, n, cur))
+        copies.append({"GiB": gib, "copy_gbps": round(n / ms / 1e6, 1), "traffic_TBps": round(2 * n / ms / 1e9, 2)})
+        print(f"# {copies[-1]}", file=sys.stderr, flush=True)
+        del a, b
+    pts = []
+    for dim, n_rows, n_idx in ((8, 10_000_000, 4_000_000), (32, 10_000_000, 4_000_000), (100, 10_000_000, 4_000_000),
+                               (128, 10_000_000, 4_000_000), (602, 2_000_000, 1_000_000),
+                               (1024, 2_500_000, 1_000_000)):
+        src = torch.empty((n_rows, dim), dtype=torch.float32, device="cuda").uniform_(-1, 1)
+        table = z.table_from_device(src.data_ptr(), n_rows, dim, "f32")
+        idx = torch.from_numpy(wl.uniform_indices(n_idx, n_rows, seed=dim)).cuda()
+        out = torch.empty((n_idx, dim), dtype=torch.float32, device="cuda")
+        rb = dim * 4
+        ms = timed(lambda: z.gather(table, idx, out, stream=cur))
+        ms_lib = timed(lambda: torch.index_select(src, 0, idx, out=out))
+        pt = {"row_bytes": rb, "out_MB": round(n_idx * rb / 1e6), "gathered_gbps": round(n_idx * rb / ms / 1e6, 1),
+              "algorithmic_traffic_TBps": round(n_idx * (2 * rb + 8) / ms / 1e9, 2),
+              "frac_of_8TBps": round(n_idx * (2 * rb + 8) / ms / 1e9 / 8.0, 3),
+              "torch_index_select_gbps": round(n_idx * rb / ms_lib / 1e6, 1)}
+        pts.append(pt)
+        print(f"# {pt}", file=sys.stderr, flush=True)
+        table.close()
+        del src, out
+    return {"plain_copy_kernel": copies, "gather": pts}
