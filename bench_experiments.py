@@ -1,6 +1,7 @@
-"""The secondary experiments of bench.py (``--config 5 ... 10``): width/dtype sweep, alignment
-sweep, resource provisioning, producer/consumer pipeline, list-length sweep and the fixed launch
-sequence behind the link's request model. The headline path (configs 1-4) stays in bench.py.
+"""The secondary experiments of bench.py (``--config 5 ... 12``): width/dtype sweep, alignment
+sweep, resource provisioning, producer/consumer pipeline, list-length sweep, the fixed launch
+sequence behind the link's request model, the request rate against table size and the HBM-resident
+variant against a plain device copy. The headline path (configs 1-4) stays in bench.py.
 
 Every function takes the parsed arguments and the modules bench.py has already imported
 (``z`` = paper_2103_03330_amd, ``wl`` = zcg_workload, numpy, torch) and returns plain data that
